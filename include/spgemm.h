@@ -1,0 +1,163 @@
+/*
+ * spgemm.h - C ABI of the MI355X (gfx950) row-wise sparse x sparse product library.
+ *
+ * The operation is the one the paper states in section 2.1, A_ij = sum_k B_ik C_kj
+ * with every matrix in compressed sparse rows (pos/crd/val arrays, 0-based), run in
+ * the row-wise loop order i -> k -> j of section 2.2 (Gustavson; "first-order
+ * scattering").  In this header the product is written C = A * B.  The paper's four
+ * workspace stages (section 4.3: insert, sort, merge, compress) are executed per
+ * output row inside on-chip workspaces; the output structure is precomputed by a
+ * symbolic phase, the route section 5.4 names for parallel workspaces.
+ *
+ * Conventions for every entry point
+ *   - All matrix arrays are DEVICE pointers on the current HIP device unless a
+ *     parameter says "host".  Input arrays are borrowed: never written, never freed.
+ *   - rowptr is int64 (rows+1 entries, rowptr[0] == 0, non-decreasing,
+ *     rowptr[rows] == nnz); colidx is int32 in [0, cols); values are float or double.
+ *     Input rows need not be sorted and may repeat a column: a repeated entry simply
+ *     contributes further products.
+ *   - Result: CSR, 0-based, columns strictly ascending inside each row, no duplicates.
+ *     An output coordinate is stored whenever at least one product lands on it, also
+ *     when the sum is exactly zero (workspaces never drop components, section 4.3).
+ *   - Every call returns an int status (0 = success, negative = spgemm_status below).
+ *     Nothing throws or aborts across this boundary.  Argument checks run before the
+ *     first HIP call, so they behave the same on a host without a GPU.
+ *   - Work is enqueued on the stream given at spgemm_create.  A handle is not
+ *     thread-safe; use one handle per host thread.
+ */
+#ifndef SPGEMM_H_
+#define SPGEMM_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  SPGEMM_OK = 0,
+  SPGEMM_INVALID_ARG = -1,     /* null pointer, negative size, bad enum */
+  SPGEMM_DIM_MISMATCH = -2,    /* A.cols != B.rows, or a plan used with other shapes */
+  SPGEMM_DTYPE_MISMATCH = -3,  /* A and B value types differ */
+  SPGEMM_UNSUPPORTED = -4,     /* a size this build cannot handle (see spgemm_symbolic) */
+  SPGEMM_ALLOC_FAILED = -5,    /* allocator callback or hipMalloc returned null */
+  SPGEMM_HIP_ERROR = -6,       /* a HIP runtime call failed; text in spgemm_last_error */
+  SPGEMM_BAD_STATE = -7,       /* plan/handle misuse */
+  SPGEMM_INVALID_INPUT = -8    /* device-side check: column out of range or rowptr not monotone */
+} spgemm_status;
+
+typedef enum { SPGEMM_F32 = 0, SPGEMM_F64 = 1 } spgemm_dtype;
+
+/* One CSR operand (section 2.1's level formats Dense, Compressed). */
+typedef struct {
+  int64_t rows, cols, nnz;
+  const int64_t* rowptr; /* device, rows+1 */
+  const int32_t* colidx; /* device, nnz (may be null when nnz == 0) */
+  const void* values;    /* device, nnz elements of dtype (may be null when nnz == 0) */
+  int32_t dtype;         /* spgemm_dtype */
+} spgemm_csr;
+
+/* Device-memory callbacks.  alloc returns a device pointer aligned to at least 256
+ * bytes or null; free releases one.  Both may be called from any API entry point on
+ * the calling thread.  When no allocator is given the library uses hipMalloc/hipFree. */
+typedef struct {
+  void* (*alloc)(void* ctx, size_t bytes);
+  void (*free)(void* ctx, void* ptr);
+  void* ctx;
+} spgemm_allocator;
+
+typedef struct spgemm_context* spgemm_handle;
+typedef struct spgemm_plan_s* spgemm_plan;
+
+/* Kernel classes for statistics (per-class accumulated time and launch count). */
+enum {
+  SPGEMM_K_COUNT = 0,  /* per-row intermediate-product count + input checks */
+  SPGEMM_K_BIN,        /* histogram, offsets, wavefront-scan scatter of row ids */
+  SPGEMM_K_SYM_ESC,    /* symbolic, sorted-list workspace (expand, sort, count unique) */
+  SPGEMM_K_SYM_HASH,   /* symbolic, LDS hash-set workspace */
+  SPGEMM_K_SYM_DENSE,  /* symbolic, LDS dense flag (bitmap) workspace */
+  SPGEMM_K_SCAN,       /* exclusive scan of row counts -> C.rowptr */
+  SPGEMM_K_NUM_ESC,    /* numeric, sorted-list workspace (expand, sort, merge duplicates) */
+  SPGEMM_K_NUM_HASH,   /* numeric, LDS hash workspace + sort */
+  SPGEMM_K_NUM_DENSE,  /* numeric, LDS dense workspace over compacted column tiles */
+  SPGEMM_NUM_KERNEL_CLASSES
+};
+
+#define SPGEMM_NUM_BINS 8
+
+typedef struct {
+  int64_t ip_total;                     /* intermediate products, sum over rows */
+  int64_t nnz_c;                        /* nonzeros of C */
+  int64_t sym_bin_rows[SPGEMM_NUM_BINS]; /* rows per symbolic bin (bin 7 = rows without products) */
+  int64_t num_bin_rows[SPGEMM_NUM_BINS]; /* rows per numeric bin (bin 7 = empty rows of C) */
+  double kernel_ms[SPGEMM_NUM_KERNEL_CLASSES];      /* summed HIP-event time of the last symbolic + numeric */
+  int32_t kernel_launches[SPGEMM_NUM_KERNEL_CLASSES];
+} spgemm_stats;
+
+/* Options for spgemm_set_option. */
+enum {
+  /* 1: bracket every kernel launch with HIP events on the handle's stream and report the
+   * times through spgemm_get_stats (adds one synchronisation per phase).  Default 0. */
+  SPGEMM_OPT_TIMING = 1,
+  /* Route rows through one workspace kind wherever its capacity allows (rows beyond that
+   * capacity keep their normal route): 0 = normal binning (default), 1 = sorted-list,
+   * 2 = hash, 3 = dense.  All routes compute the same function (the paper's table of
+   * library algorithms, section 4.4); tests use this to compare them. */
+  SPGEMM_OPT_FORCE_WORKSPACE = 2
+};
+
+/* Create a handle bound to a HIP stream (hipStream_t passed as void*, null = default
+ * stream) and an optional allocator (copied; null = hipMalloc/hipFree).  Makes no HIP call. */
+int spgemm_create(spgemm_handle* out, void* hip_stream, const spgemm_allocator* alloc);
+int spgemm_destroy(spgemm_handle h);
+int spgemm_set_option(spgemm_handle h, int option, int64_t value);
+
+/* Symbolic phase (the structure precomputation of section 5.4): counts intermediate
+ * products per row, bins rows, computes |union_k cols(B_k)| per row in per-bin
+ * workspaces and scans the counts.
+ *   c_rowptr  device, A->rows + 1 int64, caller-owned, written.
+ *   nnz_c     host, written with c_rowptr[A->rows].
+ *   plan      out; library-owned scratch (row permutations, per-row counts) that
+ *             spgemm_numeric needs.  Release with spgemm_plan_destroy.
+ * Returns after the result is on the host (one stream synchronisation).
+ * SPGEMM_UNSUPPORTED: rows, cols or a B row length of 2^31 or more.
+ * SPGEMM_INVALID_INPUT: a device-side check failed; c_rowptr contents are unspecified. */
+int spgemm_symbolic(spgemm_handle h, const spgemm_csr* A, const spgemm_csr* B,
+                    int64_t* c_rowptr, int64_t* nnz_c, spgemm_plan* plan);
+
+/* Numeric phase: for every row inserts a_ik * b_kj into the row's workspace (section 4.3
+ * insertion + deduplication), orders by column and writes the row at c_rowptr[i].
+ *   c_rowptr            device, as produced by spgemm_symbolic for this plan.
+ *   c_colidx, c_values  device, nnz_c elements each, caller-owned, written
+ *                       (may be null when nnz_c == 0).
+ * Only enqueues work (no synchronisation) unless SPGEMM_OPT_TIMING is set.  A plan may be
+ * reused for further numeric calls with new values on the same structures.
+ * Sums are accumulated in double for both value types and rounded once on output. */
+int spgemm_numeric(spgemm_handle h, spgemm_plan plan, const spgemm_csr* A, const spgemm_csr* B,
+                   const int64_t* c_rowptr, int32_t* c_colidx, void* c_values);
+
+/* Whole product.  On success C->rows/cols/nnz/dtype are set and C->rowptr/colidx/values
+ * are device buffers obtained from the handle's allocator (hipMalloc without one); the
+ * caller owns them and releases them with its allocator's free or spgemm_free_device.
+ * Synchronises once (inside the symbolic phase). */
+int spgemm(spgemm_handle h, const spgemm_csr* A, const spgemm_csr* B, spgemm_csr* C);
+
+/* Release a device buffer that spgemm() obtained (routes to the allocator's free). */
+int spgemm_free_device(spgemm_handle h, void* ptr);
+
+int spgemm_plan_destroy(spgemm_plan plan);
+
+/* Statistics of the plan's last symbolic and numeric runs (host struct, written). */
+int spgemm_get_stats(spgemm_plan plan, spgemm_stats* out);
+
+/* Text of the last error on this handle (never null; valid until the next call). */
+const char* spgemm_last_error(spgemm_handle h);
+
+/* Library version: major*10000 + minor*100 + patch. */
+int spgemm_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPGEMM_H_ */

@@ -1,0 +1,139 @@
+// Shared device helpers for the gfx950 SpGEMM kernels (wave64 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace spg {
+
+constexpr int kWave = 64;
+constexpr int kNumBins = 8;       // bins 0..6 hold work, bin 7 = rows with nothing to do
+constexpr int kEmptyBin = 7;
+constexpr int kEmptyKey = -1;     // hash-slot sentinel (column indices are >= 0)
+constexpr int kPadKey = 0x7fffffff;  // sorts behind every real column
+
+// Row classes.  Symbolic classes depend on the row's intermediate-product count ip
+// (an upper bound of its output size); numeric classes on ip and the exact output size.
+constexpr int kEscSmallCap = 32;     // bin 0: sorted-list workspace, 16 lanes per row
+constexpr int kEscLargeCap = 128;    // bin 1: sorted-list workspace, one wave per row
+constexpr int kSymHashSmall = 1024;  // bin 2: hash set with 2048 slots, one wave per row
+constexpr int kSymHashLarge = 8192;  // bin 3: hash set with 16384 slots, 256 threads per row
+constexpr int kNumHashSmall = 192;   // bin 2: hash table with 256 slots, one wave per row
+constexpr int kNumHashLarge = 1536;  // bin 3: hash table with 2048 slots, 256 threads per row
+constexpr int64_t kDenseMid = 65536;     // bins 4/5/6: dense workspace, split by ip so that
+constexpr int64_t kDenseBig = 1048576;   // the heaviest rows are scheduled first
+
+// Control block shared by host and device (one small device allocation per plan).
+struct Control {
+  unsigned hist[2][kNumBins];     // [0] symbolic, [1] numeric: rows per bin
+  unsigned offset[2][kNumBins + 1];
+  unsigned cursor[2][kNumBins];
+  unsigned work[4];               // dynamic row counters of the dense kernels
+  int error;                      // nonzero: a device-side input check failed
+  int b_sorted;                   // 1 when every B row is strictly ascending
+  unsigned long long desc_flat, desc_bnd;  // descent counts behind b_sorted
+  unsigned long long ip_total;
+  long long nnz_c;
+  long long scan_blocks;
+};
+
+__device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
+
+__device__ __forceinline__ void wave_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+template <int GROUP>
+__device__ __forceinline__ void group_sync() {
+  if constexpr (GROUP <= kWave) wave_sync(); else __syncthreads();
+}
+
+// Inclusive scan over the wave (all 64 lanes must call).
+__device__ __forceinline__ int wave_incl_scan(int v) {
+  const int l = lane_id();
+#pragma unroll
+  for (int d = 1; d < kWave; d <<= 1) {
+    int t = __shfl_up(v, d, kWave);
+    if (l >= d) v += t;
+  }
+  return v;
+}
+
+// Inclusive scan inside aligned groups of WIDTH lanes (WIDTH a power of two <= 64).
+template <int WIDTH>
+__device__ __forceinline__ int group_incl_scan(int v) {
+  const int l = threadIdx.x & (WIDTH - 1);
+#pragma unroll
+  for (int d = 1; d < WIDTH; d <<= 1) {
+    int t = __shfl_up(v, d, WIDTH);
+    if (l >= d) v += t;
+  }
+  return v;
+}
+
+__device__ __forceinline__ int wave_sum(int v) {
+#pragma unroll
+  for (int d = kWave / 2; d > 0; d >>= 1) v += __shfl_xor(v, d, kWave);
+  return v;
+}
+
+__device__ __forceinline__ unsigned hash_col(int key) { return (unsigned)key * 0x9E3779B1u; }
+
+// First position in [lo, hi) of an ascending int32 array whose value is >= target.
+__device__ __forceinline__ int64_t lower_bound_i32(const int32_t* __restrict__ a, int64_t lo, int64_t hi, int target) {
+  while (lo < hi) {
+    int64_t mid = lo + ((hi - lo) >> 1);
+    if (a[mid] < target) lo = mid + 1; else hi = mid;
+  }
+  return lo;
+}
+
+__device__ __forceinline__ int classify_symbolic(long long ip, int force) {
+  if (ip <= 0) return kEmptyBin;
+  const int dense = ip <= kDenseMid ? 4 : (ip <= kDenseBig ? 5 : 6);
+  if (force == 3) return dense;
+  if (force != 2) {
+    if (ip <= kEscSmallCap) return 0;
+    if (ip <= kEscLargeCap) return 1;
+  }
+  if (ip <= kSymHashSmall) return 2;
+  if (ip <= kSymHashLarge) return 3;
+  return dense;
+}
+
+__device__ __forceinline__ int classify_numeric(long long ip, int cnt, int force) {
+  if (cnt <= 0) return kEmptyBin;
+  const int dense = ip <= kDenseMid ? 4 : (ip <= kDenseBig ? 5 : 6);
+  if (force == 3) return dense;
+  if (force != 2) {
+    if (ip <= kEscSmallCap) return 0;
+    if (ip <= kEscLargeCap) return 1;
+  }
+  if (cnt <= kNumHashSmall) return 2;
+  if (cnt <= kNumHashLarge) return 3;
+  return dense;
+}
+
+// Bitonic sort of N (power of two) keys held in LDS by G cooperating threads
+// (thread index gl in [0, G)).  When VALS is non-null the values move with their keys.
+template <int G, typename V>
+__device__ __forceinline__ void bitonic_sort_lds(int* keys, V* vals, int n, int gl) {
+  for (int k = 2; k <= n; k <<= 1) {
+    for (int j = k >> 1; j > 0; j >>= 1) {
+      for (int t = gl; t < (n >> 1); t += G) {
+        const int i = ((t & ~(j - 1)) << 1) | (t & (j - 1));
+        const int p = i | j;
+        const int ki = keys[i], kp = keys[p];
+        const bool up = (i & k) == 0;
+        if ((ki > kp) == up) {
+          keys[i] = kp; keys[p] = ki;
+          if (vals) { V a = vals[i]; vals[i] = vals[p]; vals[p] = a; }
+        }
+      }
+      group_sync<G>();
+    }
+  }
+}
+
+}  // namespace spg

@@ -1,0 +1,246 @@
+// Per-row intermediate-product count, input checks, binning and the row-count scan.
+#pragma once
+#include "common.cuh"
+
+namespace spg {
+
+__global__ void k_init_control(Control* ctl) {
+  unsigned* w = reinterpret_cast<unsigned*>(ctl);
+  for (int i = threadIdx.x; i < (int)(sizeof(Control) / sizeof(unsigned)); i += blockDim.x) w[i] = 0;
+}
+
+// Checks B: rowptr starts at 0, is non-decreasing, ends at nnz, no row of 2^31 or more
+// entries; every column inside [0, cols).  Also counts descents (col[p] <= col[p-1]) over
+// the flat column array and descents that straddle a row boundary: every row is strictly
+// ascending exactly when the two counts agree (k_bin_offsets turns them into b_sorted).
+__global__ __launch_bounds__(256) void k_validate_b(int64_t rows, int64_t cols, int64_t nnz,
+                                                    const int64_t* __restrict__ rp, const int32_t* __restrict__ col,
+                                                    Control* ctl) {
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  const int64_t t0 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  bool bad = false;
+  int flat = 0, bnd = 0;
+  if (t0 == 0 && (rp[0] != 0 || rp[rows] != nnz)) bad = true;
+  for (int64_t i = t0; i < rows; i += stride) {
+    const int64_t a = rp[i], b = rp[i + 1];
+    if (b < a || a < 0 || b > nnz || b - a > 0x7fffffff) { bad = true; continue; }
+    if (b > a && a > 0 && col[a] <= col[a - 1]) ++bnd;
+  }
+  for (int64_t p = t0; p < nnz; p += stride) {
+    const int c = col[p];
+    if (c < 0 || c >= cols) bad = true;
+    if (p > 0 && c <= col[p - 1]) ++flat;
+  }
+  if (bad) ctl->error = 1;
+  flat = wave_sum(flat);
+  bnd = wave_sum(bnd);
+  if (lane_id() == 0) {
+    if (flat) atomicAdd(&ctl->desc_flat, (unsigned long long)flat);
+    if (bnd) atomicAdd(&ctl->desc_bnd, (unsigned long long)bnd);
+  }
+}
+
+// One workgroup of 256 threads per 256 consecutive rows of A: the chunk's A entries are
+// read coalesced, each entry adds the length of its B row to its row's counter in LDS.
+// Writes ip (saturated to int32), the symbolic bin, zero counts for rows without products.
+__global__ __launch_bounds__(256) void k_count_rows(int64_t m, int64_t nnz_a, int64_t b_rows,
+                                                    const int64_t* __restrict__ a_rp, const int32_t* __restrict__ a_col,
+                                                    const int64_t* __restrict__ b_rp, int* __restrict__ ip_out,
+                                                    unsigned char* __restrict__ bin_out, int* __restrict__ cnt_out,
+                                                    Control* ctl, int force) {
+  __shared__ long long rp[257];
+  __shared__ unsigned long long ipl[256];
+  __shared__ unsigned hist[kNumBins];
+  __shared__ int bad;
+  const int tid = threadIdx.x;
+  const int64_t r0 = (int64_t)blockIdx.x * 256;
+  const int nr = (int)((m - r0) < 256 ? (m - r0) : 256);
+  if (tid < kNumBins) hist[tid] = 0;
+  if (tid == 0) bad = 0;
+  for (int t = tid; t <= nr; t += 256) rp[t] = a_rp[r0 + t];
+  ipl[tid] = 0;
+  __syncthreads();
+  if (tid < nr && rp[tid + 1] < rp[tid]) bad = 1;
+  if (tid == 0) {
+    if (rp[0] < 0 || rp[nr] > nnz_a) bad = 1;
+    if (r0 == 0 && rp[0] != 0) bad = 1;
+    if (r0 + nr == m && rp[nr] != nnz_a) bad = 1;
+  }
+  __syncthreads();
+  if (bad) {
+    if (tid == 0) ctl->error = 1;
+    return;
+  }
+  const long long lo = rp[0], hi = rp[nr];
+  bool badcol = false;
+  for (long long p = lo + tid; p < hi; p += 256) {
+    const int k = a_col[p];
+    if (k < 0 || k >= b_rows) { badcol = true; continue; }
+    const long long len = b_rp[k + 1] - b_rp[k];
+    if (len < 0) { badcol = true; continue; }
+    // row of entry p: last t with rp[t] <= p
+    int a = 0, b = nr;
+    while (b - a > 1) {
+      const int mid = (a + b) >> 1;
+      if (rp[mid] <= p) a = mid; else b = mid;
+    }
+    if (len) atomicAdd(&ipl[a], (unsigned long long)len);
+  }
+  if (badcol) ctl->error = 1;
+  __syncthreads();
+  unsigned long long mine = 0;
+  if (tid < nr) {
+    mine = ipl[tid];
+    const int bin = classify_symbolic((long long)mine, force);
+    ip_out[r0 + tid] = mine > 0x7fffffffULL ? 0x7fffffff : (int)mine;
+    bin_out[r0 + tid] = (unsigned char)bin;
+    if (bin == kEmptyBin) cnt_out[r0 + tid] = 0;
+    atomicAdd(&hist[bin], 1u);
+  }
+  // block total of ip
+  unsigned long long s = mine;
+  for (int d = 32; d > 0; d >>= 1) s += __shfl_xor(s, d, kWave);
+  __shared__ unsigned long long wsum[4];
+  if ((tid & 63) == 0) wsum[tid >> 6] = s;
+  __syncthreads();
+  if (tid == 0) {
+    const unsigned long long tot = wsum[0] + wsum[1] + wsum[2] + wsum[3];
+    if (tot) atomicAdd(&ctl->ip_total, tot);
+  }
+  if (tid < kNumBins && hist[tid]) atomicAdd(&ctl->hist[0][tid], hist[tid]);
+}
+
+// Numeric classes from ip and the symbolic counts.
+__global__ void k_classify_numeric(int64_t m, const int* __restrict__ ip, const int* __restrict__ cnt,
+                                   unsigned char* __restrict__ bin_out, Control* ctl, int force) {
+  __shared__ unsigned hist[kNumBins];
+  if (threadIdx.x < kNumBins) hist[threadIdx.x] = 0;
+  __syncthreads();
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < m; i += stride) {
+    const int bin = classify_numeric(ip[i], cnt[i], force);
+    bin_out[i] = (unsigned char)bin;
+    atomicAdd(&hist[bin], 1u);
+  }
+  __syncthreads();
+  if (threadIdx.x < kNumBins && hist[threadIdx.x]) atomicAdd(&ctl->hist[1][threadIdx.x], hist[threadIdx.x]);
+}
+
+__global__ void k_bin_offsets(Control* ctl, int phase) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) {
+    unsigned s = 0;
+    for (int b = 0; b < kNumBins; ++b) {
+      ctl->offset[phase][b] = s;
+      s += ctl->hist[phase][b];
+      ctl->cursor[phase][b] = 0;
+    }
+    ctl->offset[phase][kNumBins] = s;
+    if (phase == 0) ctl->b_sorted = (ctl->desc_flat == ctl->desc_bnd) ? 1 : 0;
+  }
+}
+
+// Scatter row ids into their bins.  Each wave ballots per bin, its first lane of that bin
+// reserves a run with one atomic, and lanes take their rank inside the ballot mask
+// (a wavefront-level prefix count), so a bin costs one atomic per wave.
+__global__ void k_bin_scatter(int64_t m, const unsigned char* __restrict__ bin, int* __restrict__ perm,
+                              Control* ctl, int phase) {
+  if (ctl->error) return;
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const bool valid = i < m;
+  const int b = valid ? bin[i] : -1;
+  const int lane = lane_id();
+  const unsigned long long below = lane == 0 ? 0ULL : (~0ULL >> (64 - lane));
+  for (int v = 0; v < kNumBins - 1; ++v) {   // bin 7 holds rows with no work: not listed
+    const unsigned long long mask = __ballot(b == v);
+    if (mask == 0) continue;
+    const int leader = __ffsll((long long)mask) - 1;
+    unsigned base = 0;
+    if (lane == leader) base = atomicAdd(&ctl->cursor[phase][v], (unsigned)__popcll(mask));
+    base = __shfl(base, leader, kWave);
+    if (b == v) perm[ctl->offset[phase][v] + base + __popcll(mask & below)] = (int)i;
+  }
+}
+
+// ---- exclusive scan of int32 row counts into the int64 row pointer -------------------
+constexpr int kScanThreads = 256;
+constexpr int kScanItems = 16;
+constexpr int kScanTile = kScanThreads * kScanItems;
+
+__global__ __launch_bounds__(kScanThreads) void k_scan_partials(int64_t m, const int* __restrict__ cnt,
+                                                                long long* __restrict__ partial) {
+  const int64_t base = (int64_t)blockIdx.x * kScanTile;
+  long long s = 0;
+  for (int t = 0; t < kScanItems; ++t) {
+    const int64_t i = base + (int64_t)t * kScanThreads + threadIdx.x;
+    if (i < m) s += cnt[i];
+  }
+  for (int d = 32; d > 0; d >>= 1) s += __shfl_xor(s, d, kWave);
+  __shared__ long long ws[kScanThreads / kWave];
+  if ((threadIdx.x & 63) == 0) ws[threadIdx.x >> 6] = s;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    long long t = 0;
+    for (int w = 0; w < kScanThreads / kWave; ++w) t += ws[w];
+    partial[blockIdx.x] = t;
+  }
+}
+
+__global__ __launch_bounds__(kScanThreads) void k_scan_blocks(int64_t nblocks, long long* __restrict__ partial,
+                                                              int64_t m, int64_t* __restrict__ rowptr, Control* ctl) {
+  // single workgroup: exclusive scan of the per-tile sums, in place
+  __shared__ long long tile[kScanThreads];
+  __shared__ long long carry;
+  if (threadIdx.x == 0) carry = 0;
+  __syncthreads();
+  for (int64_t b0 = 0; b0 < nblocks; b0 += kScanThreads) {
+    const int64_t i = b0 + threadIdx.x;
+    const long long v = i < nblocks ? partial[i] : 0;
+    tile[threadIdx.x] = v;
+    __syncthreads();
+    for (int d = 1; d < kScanThreads; d <<= 1) {
+      long long t = threadIdx.x >= d ? tile[threadIdx.x - d] : 0;
+      __syncthreads();
+      tile[threadIdx.x] += t;
+      __syncthreads();
+    }
+    if (i < nblocks) partial[i] = carry + tile[threadIdx.x] - v;
+    __syncthreads();
+    if (threadIdx.x == 0) carry += tile[kScanThreads - 1];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    rowptr[m] = carry;
+    ctl->nnz_c = carry;
+  }
+}
+
+__global__ __launch_bounds__(kScanThreads) void k_scan_final(int64_t m, const int* __restrict__ cnt,
+                                                             const long long* __restrict__ partial,
+                                                             int64_t* __restrict__ rowptr) {
+  // thread t owns kScanItems consecutive rows of the tile
+  __shared__ long long tsum[kScanThreads];
+  const int64_t base = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * kScanItems;
+  int v[kScanItems];
+  long long s = 0;
+#pragma unroll
+  for (int t = 0; t < kScanItems; ++t) {
+    v[t] = (base + t < m) ? cnt[base + t] : 0;
+    s += v[t];
+  }
+  tsum[threadIdx.x] = s;
+  __syncthreads();
+  for (int d = 1; d < kScanThreads; d <<= 1) {
+    long long t = threadIdx.x >= d ? tsum[threadIdx.x - d] : 0;
+    __syncthreads();
+    tsum[threadIdx.x] += t;
+    __syncthreads();
+  }
+  long long run = partial[blockIdx.x] + tsum[threadIdx.x] - s;
+#pragma unroll
+  for (int t = 0; t < kScanItems; ++t) {
+    if (base + t < m) rowptr[base + t] = run;
+    run += v[t];
+  }
+}
+
+}  // namespace spg

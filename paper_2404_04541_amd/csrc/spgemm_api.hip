@@ -1,0 +1,493 @@
+// C ABI of the SpGEMM library (see include/spgemm.h): argument checks, plan scratch,
+// kernel launches.  All device work is in the *_kernels.cuh headers beside this file.
+#include "../../include/spgemm.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "common.cuh"
+#include "setup_kernels.cuh"
+#include "esc_kernels.cuh"
+#include "hash_kernels.cuh"
+#include "dense_kernels.cuh"
+
+using namespace spg;
+
+struct TimedLaunch {
+  int cls;
+  hipEvent_t start, stop;
+};
+
+struct spgemm_context {
+  hipStream_t stream = nullptr;
+  spgemm_allocator alloc{};
+  bool has_alloc = false;
+  int timing = 0;
+  int force = 0;
+  std::string err = "";
+  bool device_ready = false;
+  int num_cus = 0;
+  std::vector<TimedLaunch> timed;        // launches of the phase in flight
+  std::vector<hipEvent_t> event_pool;
+};
+
+struct spgemm_plan_s {
+  spgemm_context* h = nullptr;
+  int64_t m = 0, k = 0, n = 0, nnz_a = 0, nnz_b = 0;
+  int dtype = 0;
+  void* scratch = nullptr;
+  int* ip = nullptr;
+  int* cnt = nullptr;
+  int* perm_sym = nullptr;
+  int* perm_num = nullptr;
+  unsigned char* bin = nullptr;
+  long long* partial = nullptr;
+  Control* ctl = nullptr;
+  int64_t scan_blocks = 0;
+  bool symbolic_done = false;
+  spgemm_stats stats{};
+};
+
+namespace {
+
+int fail(spgemm_context* h, int code, const std::string& msg) {
+  if (h) h->err = msg;
+  return code;
+}
+
+#define HIP_TRY(h, expr)                                                                 \
+  do {                                                                                   \
+    hipError_t e_ = (expr);                                                              \
+    if (e_ != hipSuccess)                                                                \
+      return fail((h), SPGEMM_HIP_ERROR, std::string(#expr) + ": " + hipGetErrorString(e_)); \
+  } while (0)
+
+int check_csr(spgemm_context* h, const spgemm_csr* M, const char* name) {
+  if (!M) return fail(h, SPGEMM_INVALID_ARG, std::string(name) + " is null");
+  if (M->rows < 0 || M->cols < 0 || M->nnz < 0) return fail(h, SPGEMM_INVALID_ARG, std::string(name) + ": negative size");
+  if (M->dtype != SPGEMM_F32 && M->dtype != SPGEMM_F64) return fail(h, SPGEMM_INVALID_ARG, std::string(name) + ": unknown dtype");
+  if (!M->rowptr) return fail(h, SPGEMM_INVALID_ARG, std::string(name) + ": rowptr is null");
+  if (M->nnz > 0 && (!M->colidx || !M->values)) return fail(h, SPGEMM_INVALID_ARG, std::string(name) + ": colidx/values null with nnz > 0");
+  if (M->rows >= 0x7fffffffLL || M->cols >= 0x7fffffffLL)
+    return fail(h, SPGEMM_UNSUPPORTED, std::string(name) + ": rows and cols must be below 2^31 - 1");
+  return SPGEMM_OK;
+}
+
+int check_pair(spgemm_context* h, const spgemm_csr* A, const spgemm_csr* B) {
+  int rc = check_csr(h, A, "A");
+  if (rc) return rc;
+  rc = check_csr(h, B, "B");
+  if (rc) return rc;
+  if (A->cols != B->rows) return fail(h, SPGEMM_DIM_MISMATCH, "A.cols != B.rows");
+  if (A->dtype != B->dtype) return fail(h, SPGEMM_DTYPE_MISMATCH, "A and B value types differ");
+  return SPGEMM_OK;
+}
+
+void* dev_alloc(spgemm_context* h, size_t bytes) {
+  if (bytes == 0) bytes = 256;
+  if (h->has_alloc) return h->alloc.alloc(h->alloc.ctx, bytes);
+  void* p = nullptr;
+  if (hipMalloc(&p, bytes) != hipSuccess) return nullptr;
+  return p;
+}
+
+void dev_free(spgemm_context* h, void* p) {
+  if (!p) return;
+  if (h->has_alloc) h->alloc.free(h->alloc.ctx, p);
+  else (void)hipFree(p);
+}
+
+template <typename K>
+int allow_lds(spgemm_context* h, K kernel, size_t bytes) {
+  HIP_TRY(h, hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
+  return SPGEMM_OK;
+}
+
+int ensure_device(spgemm_context* h) {
+  if (h->device_ready) return SPGEMM_OK;
+  int dev = 0;
+  HIP_TRY(h, hipGetDevice(&dev));
+  hipDeviceProp_t prop;
+  HIP_TRY(h, hipGetDeviceProperties(&prop, dev));
+  if (prop.warpSize != kWave) return fail(h, SPGEMM_UNSUPPORTED, "device is not wave64");
+  h->num_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+  int rc;
+  if ((rc = allow_lds(h, k_sym_dense, kSymDenseLds))) return rc;
+  if ((rc = allow_lds(h, k_num_dense<float>, kNumDenseLds))) return rc;
+  if ((rc = allow_lds(h, k_num_dense<double>, kNumDenseLds))) return rc;
+  const size_t big_hash = hash_lds_bytes<256, 14, false>();
+  if ((rc = allow_lds(h, k_hash<256, 14, float, false>, big_hash))) return rc;
+  if ((rc = allow_lds(h, k_hash<256, 14, double, false>, big_hash))) return rc;
+  h->device_ready = true;
+  return SPGEMM_OK;
+}
+
+hipEvent_t take_event(spgemm_context* h) {
+  if (!h->event_pool.empty()) {
+    hipEvent_t e = h->event_pool.back();
+    h->event_pool.pop_back();
+    return e;
+  }
+  hipEvent_t e = nullptr;
+  (void)hipEventCreate(&e);
+  return e;
+}
+
+struct Timer {
+  spgemm_context* h;
+  int cls;
+  TimedLaunch t{};
+  Timer(spgemm_context* h_, int cls_) : h(h_), cls(cls_) {
+    if (h->timing) {
+      t.cls = cls;
+      t.start = take_event(h);
+      t.stop = take_event(h);
+      (void)hipEventRecord(t.start, h->stream);
+    }
+  }
+  ~Timer() {
+    if (h->timing) {
+      (void)hipEventRecord(t.stop, h->stream);
+      h->timed.push_back(t);
+    }
+  }
+};
+
+// After a stream synchronisation: fold event times into the plan's statistics.
+void collect_times(spgemm_context* h, spgemm_stats* st) {
+  for (auto& t : h->timed) {
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, t.start, t.stop) == hipSuccess) {
+      st->kernel_ms[t.cls] += ms;
+      st->kernel_launches[t.cls] += 1;
+    }
+    h->event_pool.push_back(t.start);
+    h->event_pool.push_back(t.stop);
+  }
+  h->timed.clear();
+}
+
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+inline unsigned grid_for(int64_t items, int64_t per_block, int64_t cap) {
+  int64_t g = ceil_div(items > 0 ? items : 1, per_block);
+  if (g > cap) g = cap;
+  if (g < 1) g = 1;
+  return (unsigned)g;
+}
+
+size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
+
+template <typename T>
+int run_symbolic(spgemm_context* h, spgemm_plan_s* p, const spgemm_csr* A, const spgemm_csr* B, int64_t* c_rowptr) {
+  hipStream_t s = h->stream;
+  const int64_t m = p->m;
+  const int64_t cap_small = (int64_t)h->num_cus * 32;
+  const size_t lds_hash_small = hash_lds_bytes<64, 11, false>();
+  const size_t lds_hash_large = hash_lds_bytes<256, 14, false>();
+  {
+    Timer t(h, SPGEMM_K_COUNT);
+    hipLaunchKernelGGL(k_init_control, dim3(1), dim3(64), 0, s, p->ctl);
+    hipLaunchKernelGGL(k_validate_b, dim3(grid_for(B->nnz > B->rows ? B->nnz : B->rows, 256 * 8, (int64_t)h->num_cus * 16)), dim3(256), 0, s,
+                       B->rows, B->cols, B->nnz, B->rowptr, B->colidx, p->ctl);
+    if (m > 0)
+      hipLaunchKernelGGL(k_count_rows, dim3((unsigned)ceil_div(m, 256)), dim3(256), 0, s, m, A->nnz, B->rows, A->rowptr, A->colidx,
+                         B->rowptr, p->ip, p->bin, p->cnt, p->ctl, h->force);
+  }
+  {
+    Timer t(h, SPGEMM_K_BIN);
+    hipLaunchKernelGGL(k_bin_offsets, dim3(1), dim3(64), 0, s, p->ctl, 0);
+    if (m > 0)
+      hipLaunchKernelGGL(k_bin_scatter, dim3((unsigned)ceil_div(m, 256)), dim3(256), 0, s, m, p->bin, p->perm_sym, p->ctl, 0);
+  }
+  if (m > 0) {
+    {
+      Timer t(h, SPGEMM_K_SYM_ESC);
+      hipLaunchKernelGGL((k_esc<16, 32, T, false>), dim3(grid_for(m, 16, cap_small)), dim3(256), 0, s, p->perm_sym, p->ctl, 0, 0,
+                         A->rowptr, A->colidx, (const T*)nullptr, B->rowptr, B->colidx, (const T*)nullptr, p->cnt,
+                         (const int64_t*)nullptr, (int32_t*)nullptr, (T*)nullptr);
+      hipLaunchKernelGGL((k_esc<64, 128, T, false>), dim3(grid_for(m, 4, cap_small)), dim3(256), 0, s, p->perm_sym, p->ctl, 0, 1,
+                         A->rowptr, A->colidx, (const T*)nullptr, B->rowptr, B->colidx, (const T*)nullptr, p->cnt,
+                         (const int64_t*)nullptr, (int32_t*)nullptr, (T*)nullptr);
+    }
+    {
+      Timer t(h, SPGEMM_K_SYM_HASH);
+      hipLaunchKernelGGL((k_hash<64, 11, T, false>), dim3(grid_for(m, 4, cap_small)), dim3(256), lds_hash_small, s,
+                         p->perm_sym, p->ctl, 0, 2, p->ip, A->rowptr, A->colidx, (const T*)nullptr, B->rowptr, B->colidx,
+                         (const T*)nullptr, p->cnt, (const int64_t*)nullptr, (int32_t*)nullptr, (T*)nullptr);
+      hipLaunchKernelGGL((k_hash<256, 14, T, false>), dim3(grid_for(m, 1, (int64_t)h->num_cus * 8)), dim3(256),
+                         lds_hash_large, s, p->perm_sym, p->ctl, 0, 3, p->ip, A->rowptr, A->colidx,
+                         (const T*)nullptr, B->rowptr, B->colidx, (const T*)nullptr, p->cnt, (const int64_t*)nullptr,
+                         (int32_t*)nullptr, (T*)nullptr);
+    }
+    {
+      Timer t(h, SPGEMM_K_SYM_DENSE);
+      hipLaunchKernelGGL(k_sym_dense, dim3(grid_for(m, 1, h->num_cus)), dim3(kDenseThreads), kSymDenseLds, s, p->perm_sym, p->ctl,
+                         A->rowptr, A->colidx, B->rowptr, B->colidx, B->cols, p->cnt);
+    }
+    {
+      Timer t(h, SPGEMM_K_BIN);
+      hipLaunchKernelGGL(k_classify_numeric, dim3(grid_for(m, 256, (int64_t)h->num_cus * 8)), dim3(256), 0, s, m, p->ip, p->cnt,
+                         p->bin, p->ctl, h->force);
+      hipLaunchKernelGGL(k_bin_offsets, dim3(1), dim3(64), 0, s, p->ctl, 1);
+      hipLaunchKernelGGL(k_bin_scatter, dim3((unsigned)ceil_div(m, 256)), dim3(256), 0, s, m, p->bin, p->perm_num, p->ctl, 1);
+    }
+  }
+  {
+    Timer t(h, SPGEMM_K_SCAN);
+    if (p->scan_blocks > 0)
+      hipLaunchKernelGGL(k_scan_partials, dim3((unsigned)p->scan_blocks), dim3(kScanThreads), 0, s, m, p->cnt, p->partial);
+    hipLaunchKernelGGL(k_scan_blocks, dim3(1), dim3(kScanThreads), 0, s, p->scan_blocks, p->partial, m, c_rowptr, p->ctl);
+    if (p->scan_blocks > 0)
+      hipLaunchKernelGGL(k_scan_final, dim3((unsigned)p->scan_blocks), dim3(kScanThreads), 0, s, m, p->cnt, p->partial, c_rowptr);
+  }
+  HIP_TRY(h, hipGetLastError());
+  return SPGEMM_OK;
+}
+
+__global__ void k_reset_numeric_work(Control* ctl) {
+  if (threadIdx.x == 0) ctl->work[1] = 0;
+}
+
+template <typename T>
+int run_numeric(spgemm_context* h, spgemm_plan_s* p, const spgemm_csr* A, const spgemm_csr* B, const int64_t* c_rp,
+                int32_t* c_col, void* c_val_v) {
+  hipStream_t s = h->stream;
+  const int64_t m = p->m;
+  if (m == 0) return SPGEMM_OK;
+  const int64_t cap_small = (int64_t)h->num_cus * 32;
+  const T* a_val = static_cast<const T*>(A->values);
+  const T* b_val = static_cast<const T*>(B->values);
+  T* c_val = static_cast<T*>(c_val_v);
+  const size_t lds_hash_small = hash_lds_bytes<64, 8, true>();
+  const size_t lds_hash_large = hash_lds_bytes<256, 11, true>();
+  hipLaunchKernelGGL(k_reset_numeric_work, dim3(1), dim3(64), 0, s, p->ctl);
+  {
+    Timer t(h, SPGEMM_K_NUM_ESC);
+    hipLaunchKernelGGL((k_esc<16, 32, T, true>), dim3(grid_for(m, 16, cap_small)), dim3(256), 0, s, p->perm_num, p->ctl, 1, 0,
+                       A->rowptr, A->colidx, a_val, B->rowptr, B->colidx, b_val, (int*)nullptr, c_rp, c_col, c_val);
+    hipLaunchKernelGGL((k_esc<64, 128, T, true>), dim3(grid_for(m, 4, cap_small)), dim3(256), 0, s, p->perm_num, p->ctl, 1, 1,
+                       A->rowptr, A->colidx, a_val, B->rowptr, B->colidx, b_val, (int*)nullptr, c_rp, c_col, c_val);
+  }
+  {
+    Timer t(h, SPGEMM_K_NUM_HASH);
+    hipLaunchKernelGGL((k_hash<64, 8, T, true>), dim3(grid_for(m, 4, cap_small)), dim3(256), lds_hash_small, s,
+                       p->perm_num, p->ctl, 1, 2, p->ip, A->rowptr, A->colidx, a_val, B->rowptr, B->colidx, b_val, (int*)nullptr,
+                       c_rp, c_col, c_val);
+    hipLaunchKernelGGL((k_hash<256, 11, T, true>), dim3(grid_for(m, 1, (int64_t)h->num_cus * 8)), dim3(256),
+                       lds_hash_large, s, p->perm_num, p->ctl, 1, 3, p->ip, A->rowptr, A->colidx, a_val, B->rowptr,
+                       B->colidx, b_val, (int*)nullptr, c_rp, c_col, c_val);
+  }
+  {
+    Timer t(h, SPGEMM_K_NUM_DENSE);
+    hipLaunchKernelGGL(k_num_dense<T>, dim3(grid_for(m, 1, h->num_cus)), dim3(kDenseThreads), kNumDenseLds, s, p->perm_num, p->ctl,
+                       A->rowptr, A->colidx, a_val, B->rowptr, B->colidx, b_val, B->cols, c_rp, c_col, c_val);
+  }
+  HIP_TRY(h, hipGetLastError());
+  return SPGEMM_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int spgemm_version(void) { return 100; }
+
+int spgemm_create(spgemm_handle* out, void* hip_stream, const spgemm_allocator* alloc) {
+  if (!out) return SPGEMM_INVALID_ARG;
+  if (alloc && (!alloc->alloc || !alloc->free)) return SPGEMM_INVALID_ARG;
+  spgemm_context* h = new (std::nothrow) spgemm_context();
+  if (!h) return SPGEMM_ALLOC_FAILED;
+  h->stream = static_cast<hipStream_t>(hip_stream);
+  if (alloc) {
+    h->alloc = *alloc;
+    h->has_alloc = true;
+  }
+  *out = h;
+  return SPGEMM_OK;
+}
+
+int spgemm_destroy(spgemm_handle h) {
+  if (!h) return SPGEMM_INVALID_ARG;
+  for (auto e : h->event_pool) (void)hipEventDestroy(e);
+  for (auto& t : h->timed) { (void)hipEventDestroy(t.start); (void)hipEventDestroy(t.stop); }
+  delete h;
+  return SPGEMM_OK;
+}
+
+int spgemm_set_option(spgemm_handle h, int option, int64_t value) {
+  if (!h) return SPGEMM_INVALID_ARG;
+  switch (option) {
+    case SPGEMM_OPT_TIMING:
+      if (value != 0 && value != 1) return fail(h, SPGEMM_INVALID_ARG, "timing option takes 0 or 1");
+      h->timing = (int)value;
+      return SPGEMM_OK;
+    case SPGEMM_OPT_FORCE_WORKSPACE:
+      if (value < 0 || value > 3) return fail(h, SPGEMM_INVALID_ARG, "workspace option takes 0..3");
+      h->force = (int)value;
+      return SPGEMM_OK;
+    default:
+      return fail(h, SPGEMM_INVALID_ARG, "unknown option");
+  }
+}
+
+const char* spgemm_last_error(spgemm_handle h) { return h ? h->err.c_str() : "null handle"; }
+
+int spgemm_plan_destroy(spgemm_plan p) {
+  if (!p) return SPGEMM_INVALID_ARG;
+  dev_free(p->h, p->scratch);
+  delete p;
+  return SPGEMM_OK;
+}
+
+int spgemm_get_stats(spgemm_plan p, spgemm_stats* out) {
+  if (!p || !out) return SPGEMM_INVALID_ARG;
+  if (!p->symbolic_done) return fail(p->h, SPGEMM_BAD_STATE, "plan has no symbolic result");
+  *out = p->stats;
+  return SPGEMM_OK;
+}
+
+int spgemm_symbolic(spgemm_handle h, const spgemm_csr* A, const spgemm_csr* B, int64_t* c_rowptr, int64_t* nnz_c,
+                    spgemm_plan* plan) {
+  if (!h) return SPGEMM_INVALID_ARG;
+  int rc = check_pair(h, A, B);
+  if (rc) return rc;
+  if (!c_rowptr || !nnz_c || !plan) return fail(h, SPGEMM_INVALID_ARG, "c_rowptr, nnz_c and plan must not be null");
+  *plan = nullptr;
+  if ((rc = ensure_device(h))) return rc;
+
+  spgemm_plan_s* p = new (std::nothrow) spgemm_plan_s();
+  if (!p) return fail(h, SPGEMM_ALLOC_FAILED, "host allocation failed");
+  p->h = h;
+  p->m = A->rows; p->k = A->cols; p->n = B->cols; p->nnz_a = A->nnz; p->nnz_b = B->nnz; p->dtype = A->dtype;
+  const int64_t m = p->m;
+  p->scan_blocks = m > 0 ? ceil_div(m, kScanTile) : 0;
+  size_t off = 0;
+  const size_t o_ctl = off; off = align_up(off + sizeof(Control));
+  const size_t o_ip = off; off = align_up(off + (size_t)m * 4);
+  const size_t o_cnt = off; off = align_up(off + (size_t)m * 4);
+  const size_t o_ps = off; off = align_up(off + (size_t)m * 4);
+  const size_t o_pn = off; off = align_up(off + (size_t)m * 4);
+  const size_t o_bin = off; off = align_up(off + (size_t)m);
+  const size_t o_part = off; off = align_up(off + (size_t)(p->scan_blocks + 1) * 8);
+  p->scratch = dev_alloc(h, off);
+  if (!p->scratch) {
+    delete p;
+    return fail(h, SPGEMM_ALLOC_FAILED, "device allocation of plan scratch failed");
+  }
+  unsigned char* base = static_cast<unsigned char*>(p->scratch);
+  p->ctl = reinterpret_cast<Control*>(base + o_ctl);
+  p->ip = reinterpret_cast<int*>(base + o_ip);
+  p->cnt = reinterpret_cast<int*>(base + o_cnt);
+  p->perm_sym = reinterpret_cast<int*>(base + o_ps);
+  p->perm_num = reinterpret_cast<int*>(base + o_pn);
+  p->bin = base + o_bin;
+  p->partial = reinterpret_cast<long long*>(base + o_part);
+
+  rc = (A->dtype == SPGEMM_F32) ? run_symbolic<float>(h, p, A, B, c_rowptr) : run_symbolic<double>(h, p, A, B, c_rowptr);
+  Control host{};
+  if (rc == SPGEMM_OK) {
+    hipError_t e = hipMemcpyAsync(&host, p->ctl, sizeof(Control), hipMemcpyDeviceToHost, h->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(h->stream);
+    if (e != hipSuccess) rc = fail(h, SPGEMM_HIP_ERROR, std::string("symbolic phase: ") + hipGetErrorString(e));
+  }
+  if (rc != SPGEMM_OK) {
+    (void)hipStreamSynchronize(h->stream);
+    h->timed.clear();
+    spgemm_plan_destroy(p);
+    return rc;
+  }
+  std::memset(&p->stats, 0, sizeof(p->stats));
+  collect_times(h, &p->stats);
+  if (host.error) {
+    spgemm_plan_destroy(p);
+    return fail(h, SPGEMM_INVALID_INPUT, "device-side input check failed (column out of range or rowptr not monotone)");
+  }
+  p->stats.ip_total = (int64_t)host.ip_total;
+  p->stats.nnz_c = host.nnz_c;
+  for (int b = 0; b < kNumBins; ++b) {
+    p->stats.sym_bin_rows[b] = host.hist[0][b];
+    p->stats.num_bin_rows[b] = host.hist[1][b];
+  }
+  p->symbolic_done = true;
+  *nnz_c = host.nnz_c;
+  *plan = p;
+  return SPGEMM_OK;
+}
+
+int spgemm_numeric(spgemm_handle h, spgemm_plan p, const spgemm_csr* A, const spgemm_csr* B, const int64_t* c_rowptr,
+                   int32_t* c_colidx, void* c_values) {
+  if (!h) return SPGEMM_INVALID_ARG;
+  if (!p) return fail(h, SPGEMM_INVALID_ARG, "plan is null");
+  int rc = check_pair(h, A, B);
+  if (rc) return rc;
+  if (p->h != h || !p->symbolic_done) return fail(h, SPGEMM_BAD_STATE, "plan does not belong to this handle or has no symbolic result");
+  if (A->rows != p->m || A->cols != p->k || B->cols != p->n || A->nnz != p->nnz_a || B->nnz != p->nnz_b)
+    return fail(h, SPGEMM_DIM_MISMATCH, "operands differ from the ones the plan was built for");
+  if (A->dtype != p->dtype) return fail(h, SPGEMM_DTYPE_MISMATCH, "value type differs from the plan's");
+  if (!c_rowptr) return fail(h, SPGEMM_INVALID_ARG, "c_rowptr is null");
+  if (p->stats.nnz_c > 0 && (!c_colidx || !c_values)) return fail(h, SPGEMM_INVALID_ARG, "c_colidx/c_values null with nnz_c > 0");
+  if (p->stats.nnz_c == 0) return SPGEMM_OK;
+  rc = (A->dtype == SPGEMM_F32) ? run_numeric<float>(h, p, A, B, c_rowptr, c_colidx, c_values)
+                                : run_numeric<double>(h, p, A, B, c_rowptr, c_colidx, c_values);
+  if (rc != SPGEMM_OK) return rc;
+  if (h->timing) {
+    HIP_TRY(h, hipStreamSynchronize(h->stream));
+    for (int c = SPGEMM_K_NUM_ESC; c <= SPGEMM_K_NUM_DENSE; ++c) { p->stats.kernel_ms[c] = 0; p->stats.kernel_launches[c] = 0; }
+    collect_times(h, &p->stats);
+  }
+  return SPGEMM_OK;
+}
+
+int spgemm_free_device(spgemm_handle h, void* ptr) {
+  if (!h) return SPGEMM_INVALID_ARG;
+  dev_free(h, ptr);
+  return SPGEMM_OK;
+}
+
+int spgemm(spgemm_handle h, const spgemm_csr* A, const spgemm_csr* B, spgemm_csr* C) {
+  if (!h) return SPGEMM_INVALID_ARG;
+  int rc = check_pair(h, A, B);
+  if (rc) return rc;
+  if (!C) return fail(h, SPGEMM_INVALID_ARG, "C is null");
+  std::memset(C, 0, sizeof(*C));
+  int64_t* rp = static_cast<int64_t*>(dev_alloc(h, (size_t)(A->rows + 1) * sizeof(int64_t)));
+  if (!rp) return fail(h, SPGEMM_ALLOC_FAILED, "allocation of C.rowptr failed");
+  spgemm_plan plan = nullptr;
+  int64_t nnz = 0;
+  rc = spgemm_symbolic(h, A, B, rp, &nnz, &plan);
+  if (rc != SPGEMM_OK) {
+    dev_free(h, rp);
+    return rc;
+  }
+  const size_t vsz = A->dtype == SPGEMM_F32 ? 4 : 8;
+  int32_t* col = nullptr;
+  void* val = nullptr;
+  if (nnz > 0) {
+    col = static_cast<int32_t*>(dev_alloc(h, (size_t)nnz * 4));
+    val = dev_alloc(h, (size_t)nnz * vsz);
+    if (!col || !val) {
+      dev_free(h, col); dev_free(h, val); dev_free(h, rp);
+      spgemm_plan_destroy(plan);
+      return fail(h, SPGEMM_ALLOC_FAILED, "allocation of C.colidx/C.values failed");
+    }
+    rc = spgemm_numeric(h, plan, A, B, rp, col, val);
+  }
+  // the plan's scratch may be released only after the numeric kernels that read it finish
+  if (hipStreamSynchronize(h->stream) != hipSuccess && rc == SPGEMM_OK) rc = fail(h, SPGEMM_HIP_ERROR, "numeric phase failed");
+  spgemm_plan_destroy(plan);
+  if (rc != SPGEMM_OK) {
+    dev_free(h, col); dev_free(h, val); dev_free(h, rp);
+    return rc;
+  }
+  C->rows = A->rows; C->cols = B->cols; C->nnz = nnz; C->dtype = A->dtype;
+  C->rowptr = rp; C->colidx = col; C->values = val;
+  return SPGEMM_OK;
+}
+
+}  // extern "C"

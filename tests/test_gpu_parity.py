@@ -1,0 +1,140 @@
+"""GPU parity: the HIP library (through the C ABI) against the CPU checker, element by element."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2404_04541_amd import workloads as W
+from helpers import gpu_product, assert_matches_oracle
+
+pytestmark = pytest.mark.gpu
+
+AUTO, LIST, HASH, DENSE = 0, 1, 2, 3
+
+
+def run(A, B, force=AUTO, what="", via="phases"):
+    got = gpu_product(A, B, force, via=via)
+    ref = assert_matches_oracle(A, B, got, what=what)
+    st = got[3]
+    if st is not None:
+        assert st["ip_total"] == int(ref.ip.sum())
+        assert st["nnz_c"] == int(ref.cnt.sum())
+    return st
+
+
+def test_config1_random_1000():
+    a, b = W.config1()
+    st = run(a, b, what="config1")
+    assert st["sym_bin_rows"][1] == 1000  # ip = 100 per row: the one-wave sorted-list bin
+
+
+@pytest.mark.parametrize("force", [AUTO, LIST, HASH, DENSE])
+def test_every_workspace_computes_the_same_function(force):
+    # ragged rows from empty to a few thousand products: crosses every bin boundary
+    A = W.random_csr(3000, 2500, 12, 5)
+    B = W.random_csr(2500, 4000, 30, 6)
+    run(A, B, force, what=f"ragged force={force}")
+
+
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+def test_ragged_tail_and_many_tiles(dtype):
+    A = W.random_csr(5003, 3001, 40, 7, dtype=dtype)
+    B = W.random_csr(3001, 7777, 25, 8, dtype=dtype)
+    run(A, B, what="ragged tails")
+
+
+def test_stencil_small_grid():
+    a, b = W.config2(g=12)
+    st = run(a, b, what="stencil 12^3")
+    assert st["ip_total"] == (9 * 12 - 10) ** 3 and st["nnz_c"] == (5 * 12 - 6) ** 3
+
+
+@pytest.mark.parametrize("force", [AUTO, DENSE])
+def test_rmat_small_scale_power_law(force):
+    a, b = W.config3(scale=13)
+    st = run(a, b, force, what=f"rmat scale 13 force={force}")
+    if force == AUTO:
+        assert sum(st["num_bin_rows"][4:7]) > 0, "long rows must reach the dense workspace"
+
+
+def test_rectangular_and_ttm_small():
+    a, b = W.config4(rows=20000, bcols=512)
+    run(a, b, what="config4 small")
+    a, m = W.config5(dim=64, nnz=40000)
+    run(a, m, what="config5 small")
+
+
+def test_dense_workspace_many_windows_and_tiles():
+    # wide column space (several windows) and rows with more entries than one tile holds
+    A = W.random_csr(40, 3000, 900, 11)
+    B = W.random_csr(3000, 600000, 60, 12)
+    run(A, B, DENSE, what="dense windows")
+    B2 = W.random_csr(3000, 40000, 400, 13)
+    st = run(A, B2, AUTO, what="dense tiles")
+    assert sum(st["num_bin_rows"][4:7]) > 0
+
+
+def test_unsorted_and_duplicate_inputs():
+    A = W.random_csr(400, 300, 9, 21, sort_rows=False, allow_duplicates=True)
+    B = W.random_csr(300, 500, 14, 22, sort_rows=False, allow_duplicates=True)
+    for force in (AUTO, HASH, DENSE):
+        run(A, B, force, what=f"unsorted/duplicates force={force}")
+
+
+def test_identity_and_permutation_exact():
+    A = W.random_csr(700, 700, 15, 31)
+    I = W.identity(700)
+    P = W.permutation(700, 3)
+    for X, Y in ((I, A), (A, I), (P, A), (A, P)):
+        got = gpu_product(X, Y)
+        ref = assert_matches_oracle(X, Y, got)
+        assert np.array_equal(got[2], ref.values)  # one product per entry: bit-identical values
+
+
+def test_explicit_zero_kept_and_empty_cases():
+    A = W.CSR(1, 2, np.array([0, 2]), np.array([0, 1], np.int32), np.array([1.0, 1.0]))
+    B = W.CSR(2, 2, np.array([0, 1, 3]), np.array([0, 0, 1], np.int32), np.array([1.0, -1.0, 5.0]))
+    rp, col, val, _ = gpu_product(A, B)
+    assert rp.tolist() == [0, 2] and col.tolist() == [0, 1] and val.tolist() == [0.0, 5.0]
+    Z = W.CSR(5, 4, np.zeros(6, np.int64), np.zeros(0, np.int32), np.zeros(0))
+    Bn = W.random_csr(4, 6, 2, 0)
+    for X, Y in ((Z, Bn), (W.random_csr(5, 4, 2, 1), W.CSR(4, 6, np.zeros(5, np.int64), np.zeros(0, np.int32), np.zeros(0))),
+                 (W.CSR(0, 4, np.zeros(1, np.int64), np.zeros(0, np.int32), np.zeros(0)), Bn)):
+        rp, col, val, _ = gpu_product(X, Y)
+        assert rp.tolist() == [0] * (X.rows + 1) and col.size == 0 and val.size == 0
+
+
+def test_single_call_entry_point_and_plan_reuse():
+    import torch
+    from paper_2404_04541_amd import binding as sg
+    A = W.random_csr(1500, 1200, 10, 41)
+    B = W.random_csr(1200, 1800, 12, 42)
+    run(A, B, via="single", what="spgemm()")
+    h = sg.Handle()
+    dA, dB = sg.to_device(A), sg.to_device(B)
+    rp, nnz, plan = sg.spgemm_symbolic(h, dA, dB)
+    col1, val1 = sg.spgemm_numeric(h, plan, dA, dB, rp)
+    dA2 = sg.DeviceCSR(dA.rows, dA.cols, dA.rowptr, dA.colidx, dA.values * 2.0)
+    col2, val2 = sg.spgemm_numeric(h, plan, dA2, dB, rp)
+    torch.cuda.synchronize()
+    # sums are accumulated with LDS atomics, so their order (not their structure) may change from run to run
+    assert torch.equal(col1, col2) and torch.allclose(val2, val1 * 2.0, rtol=1e-12, atol=1e-14)
+
+
+def test_invalid_input_is_reported_not_executed():
+    import torch
+    from paper_2404_04541_amd import binding as sg
+    A = W.random_csr(100, 80, 5, 51)
+    B = W.random_csr(80, 90, 5, 52)
+    h = sg.Handle()
+    dA, dB = sg.to_device(A), sg.to_device(B)
+    bad = dB.colidx.clone(); bad[3] = 90  # column == cols
+    with pytest.raises(sg.SpgemmError) as e:
+        sg.spgemm_symbolic(h, dA, sg.DeviceCSR(dB.rows, dB.cols, dB.rowptr, bad, dB.values))
+    assert e.value.status == -8
+    badrp = dA.rowptr.clone(); badrp[10] = badrp[11] + 1
+    with pytest.raises(sg.SpgemmError) as e:
+        sg.spgemm_symbolic(h, sg.DeviceCSR(dA.rows, dA.cols, badrp, dA.colidx, dA.values), dB)
+    assert e.value.status == -8
+    # the handle stays usable
+    rp, nnz, plan = sg.spgemm_symbolic(h, dA, dB)
+    assert nnz == int(oracle.spgemm(A, B).cnt.sum())

@@ -1,0 +1,141 @@
+#!/usr/bin/env python3
+"""Throughput of the whole SpGEMM hot path on one MI355X.
+
+A step is one pass of the full path (row count, binning, symbolic per bin, scan, numeric per
+bin, CSR write) over the R-MAT A*A workload: 2^20 x 2^20, fp32, 16 edges per vertex drawn,
+power-law rows.  Operands and the output buffers are resident in HBM when timing starts.
+
+Prints one JSON line:
+  value      GFLOP/s, counting 2 flops per intermediate product
+  roofline   the numeric dense-workspace kernel (the dominant one) against the 8 TB/s HBM peak,
+             from algorithmic bytes and HIP-event durations taken inside the timed region
+  cpu_baseline  the CPU checker (std::map Gustavson, all host cores) on a sample of rows
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def cpu_baseline(A, B, ip_rows: np.ndarray, budget_ip: float = 2.0e8) -> dict:
+    """Time the CPU checker on seeded random non-empty rows holding about budget_ip products."""
+    import oracle
+    from paper_2404_04541_amd import workloads as W
+    rows = np.nonzero(ip_rows > 0)[0]
+    pick = np.unique(rows[W.rand_below(0, 900, np.arange(8192, dtype=np.uint64), rows.size)])
+    order = np.argsort(W.rand_u64(0, 901, pick.astype(np.uint64)), kind="stable")
+    pick = pick[order]
+    n = int(np.searchsorted(np.cumsum(ip_rows[pick]), budget_ip)) + 1
+    pick = np.ascontiguousarray(pick[:n])
+    oracle.build()
+    t0 = time.perf_counter()
+    r = oracle.spgemm_rows(A.rowptr, A.colidx, A.values, B.rowptr, B.colidx, B.values, rows=pick)
+    dt = time.perf_counter() - t0
+    ip = int(r.ip.sum())
+    return {"value": 2.0 * ip / dt / 1e9, "unit": "GFLOP/s", "cores": oracle.max_threads(), "kind": "oracle",
+            "sample": f"{pick.size} seeded random non-empty rows of the same A*A ({ip} intermediate products, "
+                      f"{int(r.cnt.sum())} output entries), {dt:.1f} s wall"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--scale", type=int, default=20, help="R-MAT scale (20 = the benchmark configuration)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (no multi-GPU path exists); run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2404_04541_amd import workloads as W
+    from paper_2404_04541_amd import binding as sg
+    if not os.path.exists(sg.LIB_PATH):
+        from paper_2404_04541_amd.build import build_library
+        build_library()
+
+    A, B = W.config3(args.scale)
+    h = sg.Handle()
+    h.set_option(sg.OPT_TIMING, 1)
+    dA = sg.to_device(A)
+    dB = dA
+    # first pass sizes the output; its buffers are reused by every step
+    rp = torch.empty(A.rows + 1, dtype=torch.int64, device="cuda")
+    _, nnz_c, plan = sg.spgemm_symbolic(h, dA, dB, rp)
+    col = torch.empty(nnz_c, dtype=torch.int32, device="cuda")
+    val = torch.empty(nnz_c, dtype=dA.values.dtype, device="cuda")
+    sg.spgemm_numeric(h, plan, dA, dB, rp, col, val)
+    st = plan.stats()
+    plan.destroy()
+    ip_total = st["ip_total"]
+
+    def step():
+        _, n, pl = sg.spgemm_symbolic(h, dA, dB, rp)
+        assert n == nnz_c
+        sg.spgemm_numeric(h, pl, dA, dB, rp, col, val)
+        s = pl.stats()   # waits for this step's numeric kernels (event times)
+        pl.destroy()
+        return s
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    per_kernel = {}
+    for _ in range(args.steps):
+        s = step()
+        for k, v in s["kernel_ms"].items():
+            per_kernel[k] = per_kernel.get(k, 0.0) + v
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt * 1e3 / args.steps
+    gflops = 2.0 * ip_total * args.steps / dt / 1e9
+
+    v = A.values.dtype.itemsize
+    m, nnz_a = A.rows, A.nnz
+    bytes_stream = ip_total * (8 + v) + nnz_c * (4 + v) + nnz_a * (60 + v) + m * 60
+    eff_gbs = bytes_stream * args.steps / dt / 1e9
+    # dominant kernel: numeric dense workspace.  Algorithmic bytes per launch = the gathered B
+    # entries of its rows (column + value per intermediate product) + the C entries it writes.
+    dense_ip = sum(st["num_bin_ip"][4:7])
+    dense_nnz = sum(st["num_bin_nnz"][4:7])
+    dense_bytes = dense_ip * (4 + v) + dense_nnz * (4 + v)
+    dense_ms = per_kernel.get("num_dense", 0.0) / args.steps
+    achieved = dense_bytes / (dense_ms * 1e-3) / 1e9 if dense_ms > 0 else 0.0
+    out = {
+        "metric": "SpGEMM GFLOP/s (2 x intermediate products / s)", "value": gflops, "unit": "GFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32 operands, f64 accumulation", "data": "synthetic",
+        "config": {"workload": f"C=A*A, A R-MAT scale {args.scale} (a=0.57,b=c=0.19,d=0.05), 16 edges/vertex drawn, "
+                               f"duplicates merged, fp32 values U[0,1), seed 0",
+                   "rows": m, "nnz_a": nnz_a, "intermediate_products": ip_total, "nnz_c": nnz_c},
+        "effective_hbm": {"bytes_per_step": bytes_stream, "GB/s": eff_gbs, "frac_of_peak": eff_gbs / HBM_PEAK_GBS,
+                          "model": "IP*(8+v) + nnzC*(4+v) + nnzA*(60+v) + rows*60, v = value bytes"},
+        "kernel_ms_per_step": {k: per_kernel[k] / args.steps for k in per_kernel},
+        "roofline": {"kernel": "k_num_dense<float>", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "bytes_per_launch": dense_bytes, "ms_per_launch": dense_ms},
+    }
+    if not args.no_cpu_baseline:
+        run = np.concatenate([[0], np.cumsum(np.diff(B.rowptr)[A.colidx])])
+        ip_rows = run[A.rowptr[1:]] - run[A.rowptr[:-1]]
+        out["cpu_baseline"] = cpu_baseline(A, B, ip_rows)
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -91,14 +91,17 @@ typedef struct {
   int64_t nnz_c;                        /* nonzeros of C */
   int64_t sym_bin_rows[SPGEMM_NUM_BINS]; /* rows per symbolic bin (bin 7 = rows without products) */
   int64_t num_bin_rows[SPGEMM_NUM_BINS]; /* rows per numeric bin (bin 7 = empty rows of C) */
+  int64_t sym_bin_ip[SPGEMM_NUM_BINS];   /* intermediate products per symbolic bin (rows beyond 2^31-1 products saturate) */
+  int64_t num_bin_ip[SPGEMM_NUM_BINS];   /* intermediate products per numeric bin */
+  int64_t num_bin_nnz[SPGEMM_NUM_BINS];  /* entries of C per numeric bin */
   double kernel_ms[SPGEMM_NUM_KERNEL_CLASSES];      /* summed HIP-event time of the last symbolic + numeric */
   int32_t kernel_launches[SPGEMM_NUM_KERNEL_CLASSES];
 } spgemm_stats;
 
 /* Options for spgemm_set_option. */
 enum {
-  /* 1: bracket every kernel launch with HIP events on the handle's stream and report the
-   * times through spgemm_get_stats (adds one synchronisation per phase).  Default 0. */
+  /* 1: bracket every kernel class with HIP events on the handle's stream; spgemm_get_stats
+   * then waits for the recorded events and reports the times.  Default 0. */
   SPGEMM_OPT_TIMING = 1,
   /* Route rows through one workspace kind wherever its capacity allows (rows beyond that
    * capacity keep their normal route): 0 = normal binning (default), 1 = sorted-list,
@@ -131,7 +134,7 @@ int spgemm_symbolic(spgemm_handle h, const spgemm_csr* A, const spgemm_csr* B,
  *   c_rowptr            device, as produced by spgemm_symbolic for this plan.
  *   c_colidx, c_values  device, nnz_c elements each, caller-owned, written
  *                       (may be null when nnz_c == 0).
- * Only enqueues work (no synchronisation) unless SPGEMM_OPT_TIMING is set.  A plan may be
+ * Only enqueues work (no synchronisation).  A plan may be
  * reused for further numeric calls with new values on the same structures.
  * Sums are accumulated in double for both value types and rounded once on output. */
 int spgemm_numeric(spgemm_handle h, spgemm_plan plan, const spgemm_csr* A, const spgemm_csr* B,
@@ -140,7 +143,7 @@ int spgemm_numeric(spgemm_handle h, spgemm_plan plan, const spgemm_csr* A, const
 /* Whole product.  On success C->rows/cols/nnz/dtype are set and C->rowptr/colidx/values
  * are device buffers obtained from the handle's allocator (hipMalloc without one); the
  * caller owns them and releases them with its allocator's free or spgemm_free_device.
- * Synchronises once (inside the symbolic phase). */
+ * Synchronises twice: inside the symbolic phase, and before the plan's scratch is released. */
 int spgemm(spgemm_handle h, const spgemm_csr* A, const spgemm_csr* B, spgemm_csr* C);
 
 /* Release a device buffer that spgemm() obtained (routes to the allocator's free). */
@@ -148,7 +151,8 @@ int spgemm_free_device(spgemm_handle h, void* ptr);
 
 int spgemm_plan_destroy(spgemm_plan plan);
 
-/* Statistics of the plan's last symbolic and numeric runs (host struct, written). */
+/* Statistics of the plan's last symbolic and numeric runs (host struct, written).  With
+ * SPGEMM_OPT_TIMING set this waits for the stream's outstanding timed launches. */
 int spgemm_get_stats(spgemm_plan plan, spgemm_stats* out);
 
 /* Text of the last error on this handle (never null; valid until the next call). */

@@ -51,7 +51,8 @@ class AllocatorStruct(C.Structure):
 
 class StatsStruct(C.Structure):
     _fields_ = [("ip_total", C.c_int64), ("nnz_c", C.c_int64), ("sym_bin_rows", C.c_int64 * NUM_BINS),
-                ("num_bin_rows", C.c_int64 * NUM_BINS), ("kernel_ms", C.c_double * NUM_KERNEL_CLASSES),
+                ("num_bin_rows", C.c_int64 * NUM_BINS), ("sym_bin_ip", C.c_int64 * NUM_BINS),
+                ("num_bin_ip", C.c_int64 * NUM_BINS), ("num_bin_nnz", C.c_int64 * NUM_BINS), ("kernel_ms", C.c_double * NUM_KERNEL_CLASSES),
                 ("kernel_launches", C.c_int32 * NUM_KERNEL_CLASSES)]
 
 
@@ -125,6 +126,7 @@ class Plan:
         self.handle._check(self.handle.lib.spgemm_get_stats(self.ptr, C.byref(st)))
         return {"ip_total": int(st.ip_total), "nnz_c": int(st.nnz_c),
                 "sym_bin_rows": list(st.sym_bin_rows), "num_bin_rows": list(st.num_bin_rows),
+                "sym_bin_ip": list(st.sym_bin_ip), "num_bin_ip": list(st.num_bin_ip), "num_bin_nnz": list(st.num_bin_nnz),
                 "kernel_ms": dict(zip(KERNEL_CLASS_NAMES, st.kernel_ms)),
                 "kernel_launches": dict(zip(KERNEL_CLASS_NAMES, st.kernel_launches))}
 

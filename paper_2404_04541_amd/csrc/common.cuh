@@ -32,6 +32,8 @@ struct Control {
   int b_sorted;                   // 1 when every B row is strictly ascending
   unsigned long long desc_flat, desc_bnd;  // descent counts behind b_sorted
   unsigned long long ip_total;
+  unsigned long long bin_ip[2][kNumBins];   // intermediate products per bin
+  unsigned long long bin_nnz[kNumBins];     // output entries per numeric bin
   long long nnz_c;
   long long scan_blocks;
 };

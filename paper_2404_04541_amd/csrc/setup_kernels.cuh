@@ -51,11 +51,12 @@ __global__ __launch_bounds__(256) void k_count_rows(int64_t m, int64_t nnz_a, in
   __shared__ long long rp[257];
   __shared__ unsigned long long ipl[256];
   __shared__ unsigned hist[kNumBins];
+  __shared__ unsigned long long hip[kNumBins];
   __shared__ int bad;
   const int tid = threadIdx.x;
   const int64_t r0 = (int64_t)blockIdx.x * 256;
   const int nr = (int)((m - r0) < 256 ? (m - r0) : 256);
-  if (tid < kNumBins) hist[tid] = 0;
+  if (tid < kNumBins) { hist[tid] = 0; hip[tid] = 0; }
   if (tid == 0) bad = 0;
   for (int t = tid; t <= nr; t += 256) rp[t] = a_rp[r0 + t];
   ipl[tid] = 0;
@@ -96,6 +97,7 @@ __global__ __launch_bounds__(256) void k_count_rows(int64_t m, int64_t nnz_a, in
     bin_out[r0 + tid] = (unsigned char)bin;
     if (bin == kEmptyBin) cnt_out[r0 + tid] = 0;
     atomicAdd(&hist[bin], 1u);
+    if (mine) atomicAdd(&hip[bin], mine);
   }
   // block total of ip
   unsigned long long s = mine;
@@ -107,23 +109,35 @@ __global__ __launch_bounds__(256) void k_count_rows(int64_t m, int64_t nnz_a, in
     const unsigned long long tot = wsum[0] + wsum[1] + wsum[2] + wsum[3];
     if (tot) atomicAdd(&ctl->ip_total, tot);
   }
-  if (tid < kNumBins && hist[tid]) atomicAdd(&ctl->hist[0][tid], hist[tid]);
+  if (tid < kNumBins && hist[tid]) {
+    atomicAdd(&ctl->hist[0][tid], hist[tid]);
+    if (hip[tid]) atomicAdd(&ctl->bin_ip[0][tid], hip[tid]);
+  }
 }
 
 // Numeric classes from ip and the symbolic counts.
 __global__ void k_classify_numeric(int64_t m, const int* __restrict__ ip, const int* __restrict__ cnt,
                                    unsigned char* __restrict__ bin_out, Control* ctl, int force) {
   __shared__ unsigned hist[kNumBins];
-  if (threadIdx.x < kNumBins) hist[threadIdx.x] = 0;
+  __shared__ unsigned long long hip[kNumBins], hnz[kNumBins];
+  if (threadIdx.x < kNumBins) { hist[threadIdx.x] = 0; hip[threadIdx.x] = 0; hnz[threadIdx.x] = 0; }
   __syncthreads();
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < m; i += stride) {
     const int bin = classify_numeric(ip[i], cnt[i], force);
     bin_out[i] = (unsigned char)bin;
     atomicAdd(&hist[bin], 1u);
+    if (bin != kEmptyBin) {
+      atomicAdd(&hip[bin], (unsigned long long)ip[i]);
+      atomicAdd(&hnz[bin], (unsigned long long)cnt[i]);
+    }
   }
   __syncthreads();
-  if (threadIdx.x < kNumBins && hist[threadIdx.x]) atomicAdd(&ctl->hist[1][threadIdx.x], hist[threadIdx.x]);
+  if (threadIdx.x < kNumBins && hist[threadIdx.x]) {
+    atomicAdd(&ctl->hist[1][threadIdx.x], hist[threadIdx.x]);
+    atomicAdd(&ctl->bin_ip[1][threadIdx.x], hip[threadIdx.x]);
+    atomicAdd(&ctl->bin_nnz[threadIdx.x], hnz[threadIdx.x]);
+  }
 }
 
 __global__ void k_bin_offsets(Control* ctl, int phase) {

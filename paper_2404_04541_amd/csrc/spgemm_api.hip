@@ -50,6 +50,7 @@ struct spgemm_plan_s {
   Control* ctl = nullptr;
   int64_t scan_blocks = 0;
   bool symbolic_done = false;
+  bool numeric_pending = false;   // timed numeric launches not yet folded into stats
   spgemm_stats stats{};
 };
 
@@ -348,6 +349,13 @@ int spgemm_plan_destroy(spgemm_plan p) {
 int spgemm_get_stats(spgemm_plan p, spgemm_stats* out) {
   if (!p || !out) return SPGEMM_INVALID_ARG;
   if (!p->symbolic_done) return fail(p->h, SPGEMM_BAD_STATE, "plan has no symbolic result");
+  if (p->numeric_pending) {
+    spgemm_context* h = p->h;
+    if (!h->timed.empty()) HIP_TRY(h, hipEventSynchronize(h->timed.back().stop));
+    for (int c = SPGEMM_K_NUM_ESC; c <= SPGEMM_K_NUM_DENSE; ++c) { p->stats.kernel_ms[c] = 0; p->stats.kernel_launches[c] = 0; }
+    collect_times(h, &p->stats);
+    p->numeric_pending = false;
+  }
   *out = p->stats;
   return SPGEMM_OK;
 }
@@ -413,6 +421,9 @@ int spgemm_symbolic(spgemm_handle h, const spgemm_csr* A, const spgemm_csr* B, i
   for (int b = 0; b < kNumBins; ++b) {
     p->stats.sym_bin_rows[b] = host.hist[0][b];
     p->stats.num_bin_rows[b] = host.hist[1][b];
+    p->stats.sym_bin_ip[b] = (int64_t)host.bin_ip[0][b];
+    p->stats.num_bin_ip[b] = (int64_t)host.bin_ip[1][b];
+    p->stats.num_bin_nnz[b] = (int64_t)host.bin_nnz[b];
   }
   p->symbolic_done = true;
   *nnz_c = host.nnz_c;
@@ -436,11 +447,7 @@ int spgemm_numeric(spgemm_handle h, spgemm_plan p, const spgemm_csr* A, const sp
   rc = (A->dtype == SPGEMM_F32) ? run_numeric<float>(h, p, A, B, c_rowptr, c_colidx, c_values)
                                 : run_numeric<double>(h, p, A, B, c_rowptr, c_colidx, c_values);
   if (rc != SPGEMM_OK) return rc;
-  if (h->timing) {
-    HIP_TRY(h, hipStreamSynchronize(h->stream));
-    for (int c = SPGEMM_K_NUM_ESC; c <= SPGEMM_K_NUM_DENSE; ++c) { p->stats.kernel_ms[c] = 0; p->stats.kernel_launches[c] = 0; }
-    collect_times(h, &p->stats);
-  }
+  p->numeric_pending = h->timing != 0;
   return SPGEMM_OK;
 }
 

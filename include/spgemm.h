@@ -81,6 +81,7 @@ enum {
   SPGEMM_K_NUM_ESC,    /* numeric, sorted-list workspace (expand, sort, merge duplicates) */
   SPGEMM_K_NUM_HASH,   /* numeric, LDS hash workspace + sort */
   SPGEMM_K_NUM_DENSE,  /* numeric, LDS dense workspace over compacted column tiles */
+  SPGEMM_K_WINDOW_PTR, /* per-B-row column-window offsets used by the dense numeric kernel */
   SPGEMM_NUM_KERNEL_CLASSES
 };
 

@@ -47,6 +47,8 @@ struct spgemm_plan_s {
   int* perm_num = nullptr;
   unsigned char* bin = nullptr;
   long long* partial = nullptr;
+  int* win_ptr = nullptr;   // rows(B) x (num_windows + 1) offsets, null when the table would be too large
+  int num_windows = 0;
   Control* ctl = nullptr;
   int64_t scan_blocks = 0;
   bool symbolic_done = false;
@@ -206,6 +208,12 @@ int run_symbolic(spgemm_context* h, spgemm_plan_s* p, const spgemm_csr* A, const
     if (m > 0)
       hipLaunchKernelGGL(k_bin_scatter, dim3((unsigned)ceil_div(m, 256)), dim3(256), 0, s, m, p->bin, p->perm_sym, p->ctl, 0);
   }
+  if (m > 0 && p->win_ptr) {
+    Timer t(h, SPGEMM_K_WINDOW_PTR);
+    const int64_t items = B->rows * (int64_t)(p->num_windows + 1);
+    hipLaunchKernelGGL(k_window_ptrs, dim3(grid_for(items, 256, (int64_t)h->num_cus * 32)), dim3(256), 0, s, B->rows,
+                       p->num_windows, B->rowptr, B->colidx, p->ctl, p->win_ptr);
+  }
   if (m > 0) {
     {
       Timer t(h, SPGEMM_K_SYM_ESC);
@@ -287,7 +295,8 @@ int run_numeric(spgemm_context* h, spgemm_plan_s* p, const spgemm_csr* A, const 
   {
     Timer t(h, SPGEMM_K_NUM_DENSE);
     hipLaunchKernelGGL(k_num_dense<T>, dim3(grid_for(m, 1, h->num_cus)), dim3(kDenseThreads), kNumDenseLds, s, p->perm_num, p->ctl,
-                       A->rowptr, A->colidx, a_val, B->rowptr, B->colidx, b_val, B->cols, c_rp, c_col, c_val);
+                       A->rowptr, A->colidx, a_val, B->rowptr, B->colidx, b_val, B->cols, p->win_ptr, p->num_windows, c_rp, c_col,
+                       c_val);
   }
   HIP_TRY(h, hipGetLastError());
   return SPGEMM_OK;
@@ -383,6 +392,10 @@ int spgemm_symbolic(spgemm_handle h, const spgemm_csr* A, const spgemm_csr* B, i
   const size_t o_pn = off; off = align_up(off + (size_t)m * 4);
   const size_t o_bin = off; off = align_up(off + (size_t)m);
   const size_t o_part = off; off = align_up(off + (size_t)(p->scan_blocks + 1) * 8);
+  p->num_windows = (int)ceil_div(B->cols, kWinCols);
+  const size_t wp_bytes = (size_t)B->rows * (size_t)(p->num_windows + 1) * 4;
+  const bool with_wp = m > 0 && B->nnz > 0 && wp_bytes <= ((size_t)1 << 30);
+  const size_t o_wp = off; if (with_wp) off = align_up(off + wp_bytes);
   p->scratch = dev_alloc(h, off);
   if (!p->scratch) {
     delete p;
@@ -396,6 +409,7 @@ int spgemm_symbolic(spgemm_handle h, const spgemm_csr* A, const spgemm_csr* B, i
   p->perm_num = reinterpret_cast<int*>(base + o_pn);
   p->bin = base + o_bin;
   p->partial = reinterpret_cast<long long*>(base + o_part);
+  p->win_ptr = with_wp ? reinterpret_cast<int*>(base + o_wp) : nullptr;
 
   rc = (A->dtype == SPGEMM_F32) ? run_symbolic<float>(h, p, A, B, c_rowptr) : run_symbolic<double>(h, p, A, B, c_rowptr);
   Control host{};

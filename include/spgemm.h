@@ -80,8 +80,8 @@ enum {
   SPGEMM_K_SCAN,       /* exclusive scan of row counts -> C.rowptr */
   SPGEMM_K_NUM_ESC,    /* numeric, sorted-list workspace (expand, sort, merge duplicates) */
   SPGEMM_K_NUM_HASH,   /* numeric, LDS hash workspace + sort */
-  SPGEMM_K_NUM_DENSE,  /* numeric, LDS dense workspace over compacted column tiles */
-  SPGEMM_K_WINDOW_PTR, /* per-B-row column-window offsets used by the dense numeric kernel */
+  SPGEMM_K_NUM_DENSE,  /* numeric, LDS dense workspace over column tiles (direct or ranked) */
+  SPGEMM_K_BLOCK_PTR,  /* per-B-row column-block offsets used by the dense numeric kernel */
   SPGEMM_NUM_KERNEL_CLASSES
 };
 
@@ -97,6 +97,9 @@ typedef struct {
   int64_t num_bin_nnz[SPGEMM_NUM_BINS];  /* entries of C per numeric bin */
   double kernel_ms[SPGEMM_NUM_KERNEL_CLASSES];      /* summed HIP-event time of the last symbolic + numeric */
   int32_t kernel_launches[SPGEMM_NUM_KERNEL_CLASSES];
+  int64_t dense_tiles;        /* column tiles planned for the dense numeric kernel */
+  int64_t dense_direct_tiles; /* of those, tiles accumulated by column (one pass) */
+  int64_t dense_runs;         /* work items (runs of tiles of one row) */
 } spgemm_stats;
 
 /* Options for spgemm_set_option. */
@@ -108,7 +111,12 @@ enum {
    * capacity keep their normal route): 0 = normal binning (default), 1 = sorted-list,
    * 2 = hash, 3 = dense.  All routes compute the same function (the paper's table of
    * library algorithms, section 4.4); tests use this to compare them. */
-  SPGEMM_OPT_FORCE_WORKSPACE = 2
+  SPGEMM_OPT_FORCE_WORKSPACE = 2,
+  /* Dense workspace tuning: a block of 8192 columns in which a row of C has at least this
+   * many entries is accumulated in a dense array indexed by column (one pass over the
+   * products); sparser blocks are grouped and accumulated by rank (two passes).  Default 2048.
+   * Applies to the next spgemm_symbolic on the handle. */
+  SPGEMM_OPT_DIRECT_MIN = 3
 };
 
 /* Create a handle bound to a HIP stream (hipStream_t passed as void*, null = default
@@ -124,8 +132,10 @@ int spgemm_set_option(spgemm_handle h, int option, int64_t value);
  *   nnz_c     host, written with c_rowptr[A->rows].
  *   plan      out; library-owned scratch (row permutations, per-row counts) that
  *             spgemm_numeric needs.  Release with spgemm_plan_destroy.
- * Returns after the result is on the host (one stream synchronisation).
- * SPGEMM_UNSUPPORTED: rows, cols or a B row length of 2^31 or more.
+ * Returns after the result is on the host (two stream synchronisations: after the row
+ * classes are known, which sizes the plan's lists, and at the end).
+ * SPGEMM_UNSUPPORTED: rows, cols or a B row length of 2^31 or more; a B row of 2^21 or more
+ *   entries when some B row is not strictly ascending.
  * SPGEMM_INVALID_INPUT: a device-side check failed; c_rowptr contents are unspecified. */
 int spgemm_symbolic(spgemm_handle h, const spgemm_csr* A, const spgemm_csr* B,
                     int64_t* c_rowptr, int64_t* nnz_c, spgemm_plan* plan);

@@ -17,11 +17,11 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libspgemm_gfx950.so")
 
 SPGEMM_F32, SPGEMM_F64 = 0, 1
-OPT_TIMING, OPT_FORCE_WORKSPACE = 1, 2
+OPT_TIMING, OPT_FORCE_WORKSPACE, OPT_DIRECT_MIN = 1, 2, 3
 WORKSPACE_AUTO, WORKSPACE_SORTED_LIST, WORKSPACE_HASH, WORKSPACE_DENSE = 0, 1, 2, 3
 NUM_KERNEL_CLASSES = 10
 NUM_BINS = 8
-KERNEL_CLASS_NAMES = ("count", "bin", "sym_esc", "sym_hash", "sym_dense", "scan", "num_esc", "num_hash", "num_dense", "window_ptr")
+KERNEL_CLASS_NAMES = ("count", "bin", "sym_esc", "sym_hash", "sym_dense", "scan", "num_esc", "num_hash", "num_dense", "block_ptr")
 
 STATUS_NAMES = {0: "OK", -1: "INVALID_ARG", -2: "DIM_MISMATCH", -3: "DTYPE_MISMATCH", -4: "UNSUPPORTED",
                 -5: "ALLOC_FAILED", -6: "HIP_ERROR", -7: "BAD_STATE", -8: "INVALID_INPUT"}
@@ -53,7 +53,8 @@ class StatsStruct(C.Structure):
     _fields_ = [("ip_total", C.c_int64), ("nnz_c", C.c_int64), ("sym_bin_rows", C.c_int64 * NUM_BINS),
                 ("num_bin_rows", C.c_int64 * NUM_BINS), ("sym_bin_ip", C.c_int64 * NUM_BINS),
                 ("num_bin_ip", C.c_int64 * NUM_BINS), ("num_bin_nnz", C.c_int64 * NUM_BINS), ("kernel_ms", C.c_double * NUM_KERNEL_CLASSES),
-                ("kernel_launches", C.c_int32 * NUM_KERNEL_CLASSES)]
+                ("kernel_launches", C.c_int32 * NUM_KERNEL_CLASSES), ("dense_tiles", C.c_int64),
+                ("dense_direct_tiles", C.c_int64), ("dense_runs", C.c_int64)]
 
 
 _lib = None
@@ -128,7 +129,9 @@ class Plan:
                 "sym_bin_rows": list(st.sym_bin_rows), "num_bin_rows": list(st.num_bin_rows),
                 "sym_bin_ip": list(st.sym_bin_ip), "num_bin_ip": list(st.num_bin_ip), "num_bin_nnz": list(st.num_bin_nnz),
                 "kernel_ms": dict(zip(KERNEL_CLASS_NAMES, st.kernel_ms)),
-                "kernel_launches": dict(zip(KERNEL_CLASS_NAMES, st.kernel_launches))}
+                "kernel_launches": dict(zip(KERNEL_CLASS_NAMES, st.kernel_launches)),
+                "dense_tiles": int(st.dense_tiles), "dense_direct_tiles": int(st.dense_direct_tiles),
+                "dense_runs": int(st.dense_runs)}
 
     def destroy(self):
         if self.ptr:

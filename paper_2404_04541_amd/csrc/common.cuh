@@ -16,20 +16,27 @@ constexpr int kPadKey = 0x7fffffff;  // sorts behind every real column
 constexpr int kEscSmallCap = 32;     // bin 0: sorted-list workspace, 16 lanes per row
 constexpr int kEscLargeCap = 128;    // bin 1: sorted-list workspace, one wave per row
 constexpr int kSymHashSmall = 1024;  // bin 2: hash set with 2048 slots, one wave per row
-constexpr int kSymHashLarge = 8192;  // bin 3: hash set with 16384 slots, 256 threads per row
+constexpr int kSymHashLarge = 1536;  // bin 3: hash set with 4096 slots, 256 threads per row
 constexpr int kNumHashSmall = 192;   // bin 2: hash table with 256 slots, one wave per row
 constexpr int kNumHashLarge = 1536;  // bin 3: hash table with 2048 slots, 256 threads per row
 constexpr int64_t kDenseMid = 65536;     // bins 4/5/6: dense workspace, split by ip so that
 constexpr int64_t kDenseBig = 1048576;   // the heaviest rows are scheduled first
+// A row is in a dense numeric bin only if it was in a dense symbolic bin (cnt <= ip), so the
+// tile list that the dense symbolic kernel plans exists for every row the dense numeric kernel sees.
+static_assert(kSymHashLarge <= kNumHashLarge, "dense numeric rows need a dense symbolic pass");
 
 // Control block shared by host and device (one small device allocation per plan).
 struct Control {
   unsigned hist[2][kNumBins];     // [0] symbolic, [1] numeric: rows per bin
   unsigned offset[2][kNumBins + 1];
   unsigned cursor[2][kNumBins];
-  unsigned work[4];               // dynamic row counters of the dense kernels
+  unsigned work[4];               // dynamic work counters of the dense kernels
+  unsigned tile_cursor, run_cursor;   // tile / run records written by the dense symbolic kernel
+  unsigned tile_cap, run_cap;         // capacity of the two lists (set by the host)
+  unsigned direct_tiles;              // how many of the tiles are direct
   int error;                      // nonzero: a device-side input check failed
   int b_sorted;                   // 1 when every B row is strictly ascending
+  int long_b_row;                 // 1 when some B row has 2^21 or more entries
   unsigned long long desc_flat, desc_bnd;  // descent counts behind b_sorted
   unsigned long long ip_total;
   unsigned long long bin_ip[2][kNumBins];   // intermediate products per bin

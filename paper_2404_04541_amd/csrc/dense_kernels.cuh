@@ -1,16 +1,22 @@
 // Dense LDS workspaces for long rows (Gustavson's flag list / coordinate list of the
 // paper's section 4.4, and the dense first-order workspace of section 7.2), one workgroup
-// of 1024 threads per row, rows handed out heaviest class first through a device counter.
+// of 1024 threads per row.
 //
-// Symbolic: a flag list with one bit per column (up to 2^20 columns per pass in 128 KB of
-//   LDS); products set bits, the row's size is the population count.
-// Numeric : the column space is cut into windows of kWinCols columns.  Per window the flag
-//   bits are rebuilt, an exclusive prefix over the flag words gives every present column its
-//   rank, and the window's columns are cut (at flag-word granularity) into tiles of at most
-//   kTileSlots present columns.  A tile's sums live in a dense array of doubles indexed by
-//   rank - so LDS holds only columns that exist in C, and the finished tile is already in
-//   ascending column order: values stream out as one contiguous run and the column
-//   indices are decoded from the flag words (boolean indexing in the paper's words).
+// Symbolic: a flag list with one bit per column (2^20 columns per span in 128 KB of LDS);
+//   products set bits, the row's size is the population count.  From the finished flag list
+//   the kernel also plans the row's numeric work: the column space is cut at multiples of
+//   kBlkCols columns into tiles, each small enough for the numeric workspace, and the tile
+//   list is stored in the plan.
+// Numeric : one tile at a time.
+//   direct tile (one block of kBlkCols columns in which the row is dense): sums live in a
+//     dense array indexed by column, flags record which columns exist; one pass over the
+//     products, then flags and sums are compressed ("boolean indexing" in the paper's words).
+//   ranked tile (a run of blocks in which the row is sparse): pass 1 rebuilds the flag bits,
+//     an exclusive prefix over the flag words gives every present column its rank, pass 2
+//     adds a_ik * b_kj at the rank of column j - LDS holds only columns that exist in C and
+//     the finished tile is already in ascending column order.
+//   The piece of B row k that falls into a tile is found with two loads from a table of
+//   per-row block offsets (ascending B rows), so both passes touch only their own products.
 #pragma once
 #include "common.cuh"
 
@@ -21,11 +27,20 @@ constexpr int kDenseWaves = kDenseThreads / kWave;
 constexpr int kShortLen = 32;           // B-row pieces shorter than this are packed across lanes
 constexpr int kUnroll = 4;              // loads in flight per lane while walking a long piece
 constexpr int kChunk = kWave * kUnroll; // elements of a piece that one wave takes at a time
-constexpr int kSymFlagWords = 32768;    // 2^20 columns per symbolic pass (128 KB)
-constexpr int kWinCols = 131072;        // numeric window (16 KB flags + 16 KB prefix)
-constexpr int kWinWords = kWinCols / 32;
-constexpr int kTileSlots = 12288;       // doubles per numeric tile (96 KB)
-constexpr int kTileCut = kTileSlots - 32;
+constexpr int kSymFlagWords = 32768;    // 2^20 columns per symbolic span (128 KB)
+constexpr int kBlkCols = 8192;          // tile boundaries are multiples of this many columns
+constexpr int kBlkShift = 13;
+constexpr int kSpanBlocks = kSymFlagWords * 32 / kBlkCols;   // 128 blocks per symbolic span
+constexpr int kTileBudget = 135 * 1024; // LDS bytes of one numeric tile (flags + ranks + sums + columns)
+constexpr int kRankBlkBytes = kBlkCols / 32 * 8;   // flag word + rank per 32 columns of a ranked tile
+constexpr int kRankEntryBytes = 12;               // sum + column per entry of a ranked tile
+constexpr int kDirectMinDefault = 2048; // a block with at least this many entries becomes a direct tile
+constexpr int kRunTiles = 16;           // tiles handed to a workgroup at a time
+constexpr int kDirectBit = 1 << 30;     // in TileRec::cnt
+constexpr int kSegCap = 1024;           // A entries described in LDS at a time (numeric)
+
+struct TileRec { int b0, b1, cnt, out; };     // blocks [b0, b1), entries (| kDirectBit), offset inside the row of C
+struct RunRec { int row; unsigned first; int count, d; long long a0, pad; };   // tiles [first, first + count) of one row; its A entries [a0, a0 + d)
 
 // Per-workgroup bookkeeping of the piece walker below.
 struct RowScratch {
@@ -58,20 +73,17 @@ __device__ __forceinline__ void block_excl_scan2(int a, int b, int& ea, int& eb,
 }
 
 // Walks every pair (A entry p of the row, B entry q of row a_col[p]) and calls
-// f(column, product).  range(k, s, en) may narrow the piece [s, en) of B row k first
-// (f must test the column range itself when it matters).  Up to 1024 A entries are
-// described at once (one per thread); pieces of kShortLen or more are cut into chunks of
-// kChunk elements and the chunks are dealt to the 16 waves in contiguous shares, each wave
-// reading a chunk coalesced with kUnroll loads in flight per lane; the shorter pieces are
-// concatenated and walked by all threads, a thread finding its piece by a search over the
-// prefix of lengths.  Returns the number of B entries visited.  Contains barriers: every
-// thread of the workgroup must call it.
-template <bool WITH_VALUES, typename T, class Range, class F>
-__device__ __forceinline__ int stream_products(int64_t a0, int d, const int32_t* __restrict__ a_col, const T* __restrict__ a_val,
+// f(column).  range(k, s, en) may narrow the piece [s, en) of B row k first.  Up to 1024 A
+// entries are described at once (one per thread); pieces of kShortLen or more are cut into
+// chunks of kChunk elements and the chunks are dealt to the 16 waves in contiguous shares,
+// each wave reading a chunk coalesced with kUnroll loads in flight per lane; the shorter
+// pieces are concatenated and walked by all threads, a thread finding its piece by a search
+// over the prefix of lengths.  Contains barriers: every thread of the workgroup must call it.
+template <class Range, class F>
+__device__ __forceinline__ void stream_columns(int64_t a0, int d, const int32_t* __restrict__ a_col,
                                                const int64_t* __restrict__ b_rp, const int32_t* __restrict__ b_col,
-                                               const T* __restrict__ b_val, RowScratch* rs, Range range, F f) {
+                                               RowScratch* rs, Range range, F f) {
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  int visited = 0;
   for (int base = 0; base < d; base += kDenseThreads) {
     const int e = base + tid;
     int64_t s = 0;
@@ -93,7 +105,6 @@ __device__ __forceinline__ int stream_products(int64_t a0, int d, const int32_t*
     rs->spre[tid] = es;
     if (tid == 0) { rs->cpre[kDenseThreads] = tc; rs->spre[kDenseThreads] = ts; }
     __syncthreads();
-    visited += tc + ts;
     if (tc > 0) {
       const int per = (tc + kDenseWaves - 1) / kDenseWaves;
       int c = wave * per;
@@ -111,23 +122,18 @@ __device__ __forceinline__ int stream_products(int64_t a0, int d, const int32_t*
           const int64_t s_e = rs->start[ent];
           const int len_e = rs->plen[ent];
           const int cfirst = rs->cpre[ent];
-          double av = 0.0;
-          if (WITH_VALUES) av = (double)a_val[a0 + base + ent];
           const int cstop = cnext < cend ? cnext : cend;
           for (; c < cstop; ++c) {
             const int off = (c - cfirst) * kChunk + lane;
             int col[kUnroll];
-            T bv[kUnroll];
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {
               const int idx = off + u * kWave;
-              const bool ok = idx < len_e;
-              col[u] = ok ? b_col[s_e + idx] : -1;
-              if (WITH_VALUES) bv[u] = ok ? b_val[s_e + idx] : T(0);
+              col[u] = idx < len_e ? b_col[s_e + idx] : -1;
             }
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u)
-              if (col[u] >= 0) f(col[u], WITH_VALUES ? av * (double)bv[u] : 0.0);
+              if (col[u] >= 0) f(col[u]);
           }
         }
       }
@@ -138,14 +144,10 @@ __device__ __forceinline__ int stream_products(int64_t a0, int d, const int32_t*
         const int mid = (lo + hi) >> 1;
         if (rs->spre[mid] <= t) lo = mid; else hi = mid;
       }
-      const int64_t q = rs->start[lo] + (t - rs->spre[lo]);
-      double prod = 0.0;
-      if (WITH_VALUES) prod = (double)a_val[a0 + base + lo] * (double)b_val[q];
-      f(b_col[q], prod);
+      f(b_col[rs->start[lo] + (t - rs->spre[lo])]);
     }
     __syncthreads();
   }
-  return visited;
 }
 
 // Sum over the workgroup; every thread gets the result.  red: kDenseWaves ints of LDS.
@@ -160,36 +162,37 @@ __device__ __forceinline__ int block_sum(int v, int* red) {
   return s;
 }
 
-// Fetch the next row of the dense bins (4..6), heaviest class first; -1 when none is left.
-__device__ __forceinline__ int next_dense_row(const int* __restrict__ perm, Control* ctl, int phase, int* s_row) {
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    const unsigned lo = ctl->offset[phase][4], hi = ctl->offset[phase][7];
-    const unsigned idx = atomicAdd(&ctl->work[phase], 1u);
-    *s_row = idx < hi - lo ? perm[hi - 1 - idx] : -1;
-  }
-  __syncthreads();
-  return *s_row;
-}
-
-// For ascending B rows: wp[k * (nw + 1) + w] = offset inside row k of the first column that
-// is >= w * kWinCols (w = nw gives the row length).  Lets the numeric kernel cut a B row to
-// a window with two loads instead of two binary searches.
-__global__ __launch_bounds__(256) void k_window_ptrs(int64_t rows, int nw, const int64_t* __restrict__ b_rp,
-                                                     const int32_t* __restrict__ b_col, const Control* __restrict__ ctl,
-                                                     int* __restrict__ wp) {
+// For ascending B rows: bp[k * nb1 + b] = number of entries of row k with a column below
+// b * kBlkCols (b = nb1 - 1 gives the row length).  One thread per table slot: rows of at
+// most kWalkLen entries are walked once by the thread of slot 0, longer rows are bisected.
+constexpr int kWalkLen = 32;
+__global__ __launch_bounds__(256) void k_block_ptrs(int64_t rows, int nb1, const int64_t* __restrict__ b_rp,
+                                                    const int32_t* __restrict__ b_col, const Control* __restrict__ ctl,
+                                                    int* __restrict__ bp) {
   if (ctl->error || !ctl->b_sorted) return;
-  const int64_t total = rows * (nw + 1);
+  const int64_t total = rows * nb1;
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
-    const int64_t k = i / (nw + 1);
-    const int w = (int)(i - k * (nw + 1));
+    const int64_t k = i / nb1;
+    const int b = (int)(i - k * nb1);
     const int64_t s = b_rp[k], en = b_rp[k + 1];
-    int off;
-    if (w == 0) off = 0;
-    else if (w == nw) off = (int)(en - s);
-    else off = (int)(lower_bound_i32(b_col, s, en, w * kWinCols) - s);
-    wp[i] = off;
+    const int len = (int)(en - s);
+    if (len <= kWalkLen) {
+      if (b != 0) continue;
+      int* row = bp + k * nb1;
+      int nextb = 0;
+      for (int t = 0; t < len; ++t) {
+        const int cb = b_col[s + t] >> kBlkShift;
+        for (; nextb <= cb; ++nextb) row[nextb] = t;
+      }
+      for (; nextb < nb1; ++nextb) row[nextb] = len;
+    } else {
+      int off;
+      if (b == 0) off = 0;
+      else if (b == nb1 - 1) off = len;
+      else off = (int)(lower_bound_i32(b_col, s, en, b << kBlkShift) - s);
+      bp[i] = off;
+    }
   }
 }
 
@@ -198,182 +201,517 @@ struct NoRange {
 };
 
 struct SearchRange {   // binary search in an ascending row
-  const int32_t* b_col; int lo, hi;
+  const int32_t* b_col; int lo; int64_t hi;
   __device__ __forceinline__ void operator()(int, int64_t& s, int64_t& en) const {
     if (en > s) {
       s = lower_bound_i32(b_col, s, en, lo);
-      en = lower_bound_i32(b_col, s, en, hi);
+      if (hi <= 0x7fffffff) en = lower_bound_i32(b_col, s, en, (int)hi);
     }
   }
 };
 
-struct WindowRange {   // window pointers, then (optionally) a search inside the window
-  const int* wp; const int32_t* b_col; int nw1, w, lo, hi; bool narrow;
-  __device__ __forceinline__ void operator()(int k, int64_t& s, int64_t& en) const {
-    const int* row = wp + (int64_t)k * nw1;
-    en = s + row[w + 1];
-    s = s + row[w];
-    if (narrow && en > s) {
-      s = lower_bound_i32(b_col, s, en, lo);
-      en = lower_bound_i32(b_col, s, en, hi);
+// LDS of the tile planner.
+struct TilePlan {
+  int blk_cnt[kSpanBlocks];
+  int cum[kSpanBlocks + 1];
+  int nxt[kSpanBlocks];
+  TileRec rec[kSpanBlocks];
+  int ntiles, ndirect;
+  unsigned tile_base, run_base;
+  int row_out;
+};
+
+// index of the lowest set bit at or above position b in the 128-bit mask (hi:lo); 128 when none
+__device__ __forceinline__ int next_bit128(unsigned long long lo, unsigned long long hi, int b) {
+  if (b < 64) {
+    const unsigned long long m = lo >> b;
+    if (m) return b + __ffsll((long long)m) - 1;
+    if (hi) return 64 + __ffsll((long long)hi) - 1;
+    return 128;
+  }
+  if (b >= 128) return 128;
+  const unsigned long long m = hi >> (b - 64);
+  return m ? b + __ffsll((long long)m) - 1 : 128;
+}
+
+// index of the highest set bit below position e; -1 when none
+__device__ __forceinline__ int prev_bit128(unsigned long long lo, unsigned long long hi, int e) {
+  if (e > 64) {
+    const unsigned long long m = e >= 128 ? hi : (hi & ((1ULL << (e - 64)) - 1ULL));
+    if (m) return 127 - __clzll((long long)m);
+    e = 64;
+  }
+  if (e <= 0) return -1;
+  const unsigned long long m = e >= 64 ? lo : (lo & ((1ULL << e) - 1ULL));
+  return m ? 63 - __clzll((long long)m) : -1;
+}
+
+// Cuts the nb blocks of one span (counts in tp->blk_cnt) into tiles; run by wave 0.
+// A block with at least direct_min entries is a direct tile of its own; the blocks between
+// are grouped greedily into ranked tiles of at most kTileBudget bytes
+// (kRankBlkBytes per block + kRankEntryBytes per entry).  Records land in tp->rec, their number in tp->ntiles.
+__device__ __forceinline__ void plan_tiles(TilePlan* tp, int nb, int block0, int direct_min) {
+  const int l = lane_id();
+  const int c0 = l < nb ? tp->blk_cnt[l] : 0;
+  const int c1 = l + 64 < nb ? tp->blk_cnt[l + 64] : 0;
+  const int i0 = wave_incl_scan(c0);
+  const int t0 = __shfl(i0, 63, kWave);
+  const int i1 = wave_incl_scan(c1);
+  tp->cum[l] = i0 - c0;
+  tp->cum[l + 64] = t0 + i1 - c1;
+  if (l == 63) tp->cum[128] = t0 + i1;
+  const unsigned long long dm0 = __ballot(c0 >= direct_min), dm1 = __ballot(c1 >= direct_min);
+  const unsigned long long nm0 = __ballot(c0 > 0), nm1 = __ballot(c1 > 0);
+  wave_sync();
+#pragma unroll
+  for (int half = 0; half < 2; ++half) {
+    const int b = l + 64 * half;
+    if (b < nb) {
+      int lim = next_bit128(dm0, dm1, b);   // first direct block at or behind b
+      if (lim > nb) lim = nb;
+      const int base = tp->cum[b];
+      int lo = b + 1, hi = lim;             // largest e in [b+1, lim] that fits
+      while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if ((long long)(mid - b) * kRankBlkBytes + (long long)kRankEntryBytes * (tp->cum[mid] - base) <= kTileBudget) lo = mid; else hi = mid - 1;
+      }
+      tp->nxt[b] = lo;
     }
   }
-};
+  wave_sync();
+  if (l == 0) {
+    int n = 0, out = tp->row_out;
+    int b = next_bit128(nm0, nm1, 0);
+    while (b < nb) {
+      const int cb = tp->blk_cnt[b];
+      if (cb >= direct_min) {
+        tp->rec[n++] = TileRec{block0 + b, block0 + b + 1, cb | kDirectBit, out};
+        out += cb;
+        b = b + 1;
+      } else {
+        const int e = tp->nxt[b];
+        const int c = tp->cum[e] - tp->cum[b];
+        const int et = prev_bit128(nm0, nm1, e) + 1;   // drop empty blocks at the end
+        tp->rec[n++] = TileRec{block0 + b, block0 + et, c, out};
+        out += c;
+        b = e;
+      }
+      b = next_bit128(nm0, nm1, b);
+    }
+    tp->ntiles = n;
+    tp->ndirect = __popcll(dm0) + __popcll(dm1);
+    tp->row_out = out;
+  }
+}
+
+// Fetch the next row of the dense symbolic bins (4..6), heaviest class first; -1 when none is left.
+__device__ __forceinline__ int next_dense_row(const int* __restrict__ perm, Control* ctl, int* s_row) {
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const unsigned lo = ctl->offset[0][4], hi = ctl->offset[0][7];
+    const unsigned idx = atomicAdd(&ctl->work[0], 1u);
+    *s_row = idx < hi - lo ? perm[hi - 1 - idx] : -1;
+  }
+  __syncthreads();
+  return *s_row;
+}
 
 __global__ __launch_bounds__(kDenseThreads) void k_sym_dense(const int* __restrict__ perm, Control* ctl,
                                                              const int64_t* __restrict__ a_rp, const int32_t* __restrict__ a_col,
                                                              const int64_t* __restrict__ b_rp, const int32_t* __restrict__ b_col,
-                                                             int64_t n_cols, int* __restrict__ cnt) {
+                                                             int64_t n_cols, int* __restrict__ cnt,
+                                                             TileRec* __restrict__ tiles, RunRec* __restrict__ runs, int direct_min) {
   extern __shared__ __align__(16) unsigned char smem[];
   unsigned* flags = reinterpret_cast<unsigned*>(smem);                               // kSymFlagWords
   RowScratch* rs = reinterpret_cast<RowScratch*>(smem + (size_t)kSymFlagWords * 4);
+  TilePlan* tp = reinterpret_cast<TilePlan*>(smem + (size_t)kSymFlagWords * 4 + sizeof(RowScratch));
   if (ctl->error) return;
   const bool sorted = ctl->b_sorted != 0;
   const int64_t span = (int64_t)kSymFlagWords * 32;
+  const int tid = threadIdx.x;
   while (true) {
-    const int row = next_dense_row(perm, ctl, 0, &rs->s_row);
+    const int row = next_dense_row(perm, ctl, &rs->s_row);
     if (row < 0) break;
     const int64_t a0 = a_rp[row];
     const int d = (int)(a_rp[row + 1] - a0);
-    int total = 0;
+    if (tid == 0) tp->row_out = 0;
     for (int64_t c0 = 0; c0 < n_cols; c0 += span) {
       const int64_t c1 = (c0 + span < n_cols) ? c0 + span : n_cols;
       const int words = (int)((c1 - c0 + 31) >> 5);
-      for (int w = threadIdx.x; w < words; w += kDenseThreads) flags[w] = 0;
+      const int nb = (int)((c1 - c0 + kBlkCols - 1) >> kBlkShift);
+      {
+        uint4* f4 = reinterpret_cast<uint4*>(flags);
+        for (int w = tid; w < kSymFlagWords / 4; w += kDenseThreads) f4[w] = make_uint4(0, 0, 0, 0);
+      }
+      if (tid < kSpanBlocks) tp->blk_cnt[tid] = 0;
       __syncthreads();
-      const int lo = (int)c0, hi = (int)c1;
-      auto mark = [&](int c, double) {
-        if (c >= lo && c < hi) atomicOr(&flags[(c - lo) >> 5], 1u << ((c - lo) & 31));
+      const int lo = (int)c0;
+      const int64_t hi = c1;
+      auto mark = [&](int c) {
+        if (c >= lo && (int64_t)c < hi) atomicOr(&flags[(c - lo) >> 5], 1u << ((c - lo) & 31));
       };
       if (n_cols > span && sorted)
-        stream_products<false, float>(a0, d, a_col, nullptr, b_rp, b_col, nullptr, rs, SearchRange{b_col, lo, hi}, mark);
+        stream_columns(a0, d, a_col, b_rp, b_col, rs, SearchRange{b_col, lo, hi}, mark);
       else
-        stream_products<false, float>(a0, d, a_col, nullptr, b_rp, b_col, nullptr, rs, NoRange{}, mark);
-      int local = 0;
-      for (int w = threadIdx.x; w < words; w += kDenseThreads) local += __popc(flags[w]);
-      total += block_sum(local, rs->red);
+        stream_columns(a0, d, a_col, b_rp, b_col, rs, NoRange{}, mark);
+      // entries per block: thread t owns flag words [32 t, 32 t + 32), 8 threads per block
+      {
+        const uint4* f4 = reinterpret_cast<const uint4*>(flags) + tid * 8;
+        int local = 0;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+          const uint4 v = f4[q];
+          local += __popc(v.x) + __popc(v.y) + __popc(v.z) + __popc(v.w);
+        }
+        local += __shfl_xor(local, 1, kWave);
+        local += __shfl_xor(local, 2, kWave);
+        local += __shfl_xor(local, 4, kWave);
+        if ((tid & 7) == 0) tp->blk_cnt[tid >> 3] = local;
+      }
+      __syncthreads();
+      if (tid < kWave) plan_tiles(tp, nb, (int)(c0 >> kBlkShift), direct_min);
+      __syncthreads();
+      const int nt = tp->ntiles;
+      const int nr = (nt + kRunTiles - 1) / kRunTiles;
+      if (tid == 0 && nt > 0) {
+        tp->tile_base = atomicAdd(&ctl->tile_cursor, (unsigned)nt);
+        tp->run_base = atomicAdd(&ctl->run_cursor, (unsigned)nr);
+        if (tp->ndirect) atomicAdd(&ctl->direct_tiles, (unsigned)tp->ndirect);
+        if (tp->tile_base + (unsigned)nt > ctl->tile_cap || tp->run_base + (unsigned)nr > ctl->run_cap) {
+          ctl->error = 3;   // cannot happen when the host sized the lists from the bound
+          tp->ntiles = 0;
+        }
+      }
+      __syncthreads();
+      if (tp->ntiles > 0) {
+        if (tid < nt) tiles[tp->tile_base + tid] = tp->rec[tid];
+        if (tid < nr) {
+          const int left = nt - tid * kRunTiles;
+          runs[tp->run_base + tid] = RunRec{row, tp->tile_base + (unsigned)(tid * kRunTiles), left < kRunTiles ? left : kRunTiles, d, a0, 0};
+        }
+      }
+      __syncthreads();
     }
-    if (threadIdx.x == 0) cnt[row] = total;
+    if (tid == 0) cnt[row] = tp->row_out;
   }
 }
 
-constexpr size_t kSymDenseLds = (size_t)kSymFlagWords * 4 + sizeof(RowScratch);
+constexpr size_t kSymDenseLds = (size_t)kSymFlagWords * 4 + sizeof(RowScratch) + sizeof(TilePlan);
+
+// ---- numeric --------------------------------------------------------------------------
+
+// LDS behind the tile area of the numeric kernel.
+template <typename T>
+struct NumScratch {
+  long long c_s[kSegCap];      // first B entry of every non-empty piece of the tile
+  int c_cpre[kSegCap + 1];     // exclusive prefix of the pieces' chunk counts
+  int c_len[kSegCap];          // piece length
+  T c_av[kSegCap];             // a_ik of the piece
+  TileRec rec[kRunTiles];
+  int red[2 * kDenseWaves];
+  int s_run;
+  int pad;
+};
+
+constexpr int kChunkUnroll = 8;
+
+__device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ long long uni64(long long v) {
+  const unsigned lo = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(unsigned long long)v);
+  const unsigned hi = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)((unsigned long long)v >> 32));
+  return (long long)(((unsigned long long)hi << 32) | lo);
+}
+
+// Visits every element of the pieces once.  A piece is cut into chunks of 64 elements; the
+// chunks of all pieces are dealt to the waves in contiguous shares; a wave reads a chunk
+// coalesced (one element per lane) with kChunkUnroll chunks in flight, and everything that
+// describes a chunk is wave-uniform.  f(column, a, b) is called per element (a, b only
+// meaningful when WITH_VALUES).
+template <bool WITH_VALUES, typename T, class F>
+__device__ __forceinline__ void chunk_pass(int np, int nchunks, const NumScratch<T>* ns, const int32_t* __restrict__ b_col,
+                                           const T* __restrict__ b_val, F f) {
+  const int wave = uni(threadIdx.x >> 6), lane = threadIdx.x & 63;
+  np = uni(np);
+  nchunks = uni(nchunks);
+  const int per = (nchunks + kDenseWaves - 1) / kDenseWaves;
+  int c = wave * per;
+  const int cend = c + per < nchunks ? c + per : nchunks;
+  if (c >= cend) return;
+  int p;
+  {
+    int lo = 0, hi = np;   // last piece whose first chunk is <= c
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (uni(ns->c_cpre[mid]) <= c) lo = mid; else hi = mid;
+    }
+    p = lo;
+  }
+  int cfirst = uni(ns->c_cpre[p]), cnext = uni(ns->c_cpre[p + 1]);
+  int len = uni(ns->c_len[p]);
+  long long s = uni64(ns->c_s[p]);
+  T av = WITH_VALUES ? ns->c_av[p] : T(0);
+  for (; c < cend; c += kChunkUnroll) {
+    int col[kChunkUnroll];
+    T bv[kChunkUnroll], au[kChunkUnroll];
+#pragma unroll
+    for (int u = 0; u < kChunkUnroll; ++u) {
+      const int cu = c + u;
+      col[u] = -1;
+      bv[u] = T(0);
+      au[u] = av;
+      if (cu < cend) {
+        if (cu >= cnext) {   // every piece has at least one chunk: one step suffices
+          ++p;
+          cfirst = cnext;
+          cnext = uni(ns->c_cpre[p + 1]);
+          len = uni(ns->c_len[p]);
+          s = uni64(ns->c_s[p]);
+          if (WITH_VALUES) av = ns->c_av[p];
+        }
+        const int off = (cu - cfirst) * kWave + lane;
+        if (off < len) {
+          col[u] = b_col[s + off];
+          if (WITH_VALUES) bv[u] = b_val[s + off];
+        }
+        au[u] = av;
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < kChunkUnroll; ++u)
+      if (col[u] >= 0) f(col[u], au[u], bv[u]);
+  }
+}
+
+// The piece [s, s + len) of B row k that falls into the tile (blocks [b0, b1), columns [t_lo, t_hi)).
+__device__ __forceinline__ void piece_range(int k, long long rs, long long re, int b0, int b1, int t_lo, int64_t t_hi, bool sorted,
+                                            const int* __restrict__ bp, int nb1, const int32_t* __restrict__ b_col,
+                                            long long& s, int& len) {
+  if (sorted && bp) {
+    const int* row = bp + (int64_t)k * nb1;
+    const int o0 = row[b0], o1 = row[b1];
+    s = rs + o0;
+    len = o1 - o0;
+  } else {
+    int64_t st = rs, en = re;
+    if (sorted) SearchRange{b_col, t_lo, t_hi}(k, st, en);
+    s = st;
+    len = (int)(en - st);
+  }
+}
+
+// Compacts the non-empty pieces of the workgroup's threads into c_s / c_cpre / c_len / c_av.
+// Returns their number and the chunk total.  Contains barriers.
+template <typename T>
+__device__ __forceinline__ void tile_pieces(NumScratch<T>* ns, long long s, int len, T av, int& np, int& nchunks) {
+  int idx, cpre;
+  block_excl_scan2(len > 0 ? 1 : 0, (len + kWave - 1) >> 6, idx, cpre, np, nchunks, ns->red);
+  if (len > 0) {
+    ns->c_s[idx] = s;
+    ns->c_cpre[idx] = cpre;
+    ns->c_len[idx] = len;
+    ns->c_av[idx] = av;
+  }
+  if (threadIdx.x == 0) ns->c_cpre[np] = nchunks;
+  __syncthreads();
+}
+
+template <typename T, bool CHECK>
+__device__ __forceinline__ void num_dense_run(const RunRec rr, NumScratch<T>* ns, unsigned char* tile, bool sorted,
+                                              const int32_t* __restrict__ a_col, const T* __restrict__ a_val,
+                                              const int64_t* __restrict__ b_rp, const int32_t* __restrict__ b_col,
+                                              const T* __restrict__ b_val, int64_t n_cols, const int* __restrict__ bp, int nb1,
+                                              int64_t out_row, int32_t* __restrict__ c_col, T* __restrict__ c_val) {
+  const int tid = threadIdx.x;
+  const int64_t a0 = rr.a0;
+  const int d = rr.d;
+  const int nseg = (d + kSegCap - 1) / kSegCap;
+  // with one segment, thread e keeps A entry e in registers for the whole run
+  int my_k = 0;
+  long long my_rs = 0, my_re = 0;
+  T my_av = T(0);
+  if (nseg == 1 && tid < d) {
+    my_k = a_col[a0 + tid];
+    my_av = a_val[a0 + tid];
+    my_rs = b_rp[my_k];
+    my_re = b_rp[my_k + 1];
+  }
+  for (int t = 0; t < rr.count; ++t) {
+    const TileRec tr = ns->rec[t];
+    const bool direct = (tr.cnt & kDirectBit) != 0;
+    const int count = tr.cnt & (kDirectBit - 1);
+    const int t_lo = tr.b0 << kBlkShift;
+    int64_t t_hi = (int64_t)tr.b1 << kBlkShift;
+    if (t_hi > n_cols) t_hi = n_cols;
+    const int64_t out = out_row + tr.out;
+    // this thread's piece of the tile (one segment), or per segment below
+    long long s = 0;
+    int len = 0;
+    if (nseg == 1 && tid < d) piece_range(my_k, my_rs, my_re, tr.b0, tr.b1, t_lo, t_hi, sorted, bp, nb1, b_col, s, len);
+    auto seg_piece = [&](int sg, long long& ps, int& plen, T& pav) {
+      ps = 0; plen = 0; pav = T(0);
+      const int e = sg * kSegCap + tid;
+      if (e < d && e < (sg + 1) * kSegCap) {
+        const int k = a_col[a0 + e];
+        pav = a_val[a0 + e];
+        piece_range(k, b_rp[k], b_rp[k + 1], tr.b0, tr.b1, t_lo, t_hi, sorted, bp, nb1, b_col, ps, plen);
+      }
+    };
+    __syncthreads();   // the previous tile's output has left the tile area
+    if (direct) {
+      double* acc = reinterpret_cast<double*>(tile);                      // kBlkCols sums, indexed by column
+      int* stage = reinterpret_cast<int*>(tile + (size_t)kBlkCols * 8);   // kBlkCols columns, by rank
+      unsigned* flags = reinterpret_cast<unsigned*>(tile + (size_t)kBlkCols * 12);   // kBlkCols / 32
+      {
+        double2* a2 = reinterpret_cast<double2*>(acc);
+        for (int r = tid; r < kBlkCols / 2; r += kDenseThreads) a2[r] = make_double2(0.0, 0.0);
+      }
+      if (tid < kBlkCols / 32) flags[tid] = 0;
+      for (int sg = 0; sg < nseg; ++sg) {
+        T av = my_av;
+        if (nseg > 1) seg_piece(sg, s, len, av);
+        int np, nchunks;
+        tile_pieces(ns, s, len, av, np, nchunks);
+        chunk_pass<true, T>(np, nchunks, ns, b_col, b_val, [&](int c, T a, T b) {
+          if (!CHECK || (c >= t_lo && (int64_t)c < t_hi)) {
+            const int rel = c - t_lo;
+            atomicOr(&flags[rel >> 5], 1u << (rel & 31));
+            __hip_atomic_fetch_add(&acc[rel], (double)a * (double)b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+          }
+        });
+        if (nseg > 1) __syncthreads();
+      }
+      __syncthreads();
+      // compress: thread t owns columns [8 t, 8 t + 8)
+      const unsigned byte = (flags[tid >> 2] >> ((tid & 3) * 8)) & 255u;
+      double v[8];
+      {
+        const double2* a2 = reinterpret_cast<const double2*>(acc) + tid * 4;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { const double2 x = a2[i]; v[2 * i] = x.x; v[2 * i + 1] = x.y; }
+      }
+      int base, dummy_e, tot, dummy_t;
+      block_excl_scan2(__popc(byte), 0, base, dummy_e, tot, dummy_t, ns->red);   // barriers: every sum has been read
+      (void)tot;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        if (byte & (1u << i)) {
+          acc[base] = v[i];
+          stage[base] = t_lo + tid * 8 + i;
+          ++base;
+        }
+      }
+      __syncthreads();
+      for (int r = tid; r < count; r += kDenseThreads) {
+        c_val[out + r] = (T)acc[r];
+        c_col[out + r] = stage[r];
+      }
+    } else {
+      const int nw = (tr.b1 - tr.b0) * (kBlkCols / 32);                   // 32-bit flag words
+      uint2* fc = reinterpret_cast<uint2*>(tile);                         // per word: .x flag bits, .y rank of its first column
+      double* acc = reinterpret_cast<double*>(tile + (size_t)nw * 8);     // count sums, by rank
+      int* stage = reinterpret_cast<int*>(acc + count);                   // count columns, by rank
+      for (int w = tid; w < nw; w += kDenseThreads) fc[w] = make_uint2(0u, 0u);
+      // pass 1: which columns of the tile exist in the row
+      int np = 0, nchunks = 0;
+      for (int sg = 0; sg < nseg; ++sg) {
+        T av = my_av;
+        if (nseg > 1) seg_piece(sg, s, len, av);
+        tile_pieces(ns, s, len, av, np, nchunks);
+        chunk_pass<false, T>(np, nchunks, ns, b_col, b_val, [&](int c, T, T) {
+          if (!CHECK || (c >= t_lo && (int64_t)c < t_hi)) {
+            const int rel = c - t_lo;
+            atomicOr(&fc[rel >> 5].x, 1u << (rel & 31));
+          }
+        });
+        if (nseg > 1) __syncthreads();
+      }
+      // exclusive prefix of the flag-word populations (consecutive words per thread)
+      const int per = (nw + kDenseThreads - 1) / kDenseThreads;
+      const int w0 = tid * per;
+      __syncthreads();
+      int mine = 0;
+      for (int w = w0; w < w0 + per && w < nw; ++w) mine += __popc(fc[w].x);
+      int excl, dummy_e, win_total, dummy_t;
+      block_excl_scan2(mine, 0, excl, dummy_e, win_total, dummy_t, ns->red);
+      (void)win_total;
+      for (int w = w0; w < w0 + per && w < nw; ++w) {
+        unsigned bits = fc[w].x;
+        fc[w].y = (unsigned)excl;
+        const int cbase = t_lo + w * 32;
+        while (bits) {   // columns are decoded from the flag words ("boolean indexing")
+          const int b = __ffs((int)bits) - 1;
+          bits &= bits - 1;
+          stage[excl++] = cbase + b;
+        }
+      }
+      for (int r = tid; r < count; r += kDenseThreads) acc[r] = 0.0;
+      __syncthreads();
+      // pass 2: accumulate a_ik * b_kj at the rank of column j
+      for (int sg = 0; sg < nseg; ++sg) {
+        if (nseg > 1) {
+          T av;
+          seg_piece(sg, s, len, av);
+          tile_pieces(ns, s, len, av, np, nchunks);
+        }
+        chunk_pass<true, T>(np, nchunks, ns, b_col, b_val, [&](int c, T a, T b) {
+          if (!CHECK || (c >= t_lo && (int64_t)c < t_hi)) {
+            const int rel = c - t_lo;
+            const uint2 w = fc[rel >> 5];
+            const int rank = (int)w.y + __popc(w.x & ((1u << (rel & 31)) - 1u));
+            __hip_atomic_fetch_add(&acc[rank], (double)a * (double)b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+          }
+        });
+        if (nseg > 1) __syncthreads();
+      }
+      __syncthreads();
+      // compress: sums and columns are already in ascending column order
+      for (int r = tid; r < count; r += kDenseThreads) {
+        c_val[out + r] = (T)acc[r];
+        c_col[out + r] = stage[r];
+      }
+    }
+  }
+}
 
 template <typename T>
-__global__ __launch_bounds__(kDenseThreads) void k_num_dense(const int* __restrict__ perm, Control* ctl,
-                                                             const int64_t* __restrict__ a_rp, const int32_t* __restrict__ a_col,
+__global__ __launch_bounds__(kDenseThreads) void k_num_dense(Control* ctl, const unsigned char* __restrict__ numbin,
+                                                             const TileRec* __restrict__ tiles, const RunRec* __restrict__ runs,
+                                                             const int32_t* __restrict__ a_col,
                                                              const T* __restrict__ a_val, const int64_t* __restrict__ b_rp,
                                                              const int32_t* __restrict__ b_col, const T* __restrict__ b_val,
-                                                             int64_t n_cols, const int* __restrict__ wp, int nw,
+                                                             int64_t n_cols, const int* __restrict__ bp, int nb1,
                                                              const int64_t* __restrict__ c_rp,
                                                              int32_t* __restrict__ c_col, T* __restrict__ c_val) {
   extern __shared__ __align__(16) unsigned char smem[];
-  double* acc = reinterpret_cast<double*>(smem);                                     // kTileSlots
-  unsigned* flags = reinterpret_cast<unsigned*>(smem + (size_t)kTileSlots * 8);      // kWinWords
-  unsigned* cum = flags + kWinWords;                                                 // kWinWords + 1 (+3 pad)
-  RowScratch* rs = reinterpret_cast<RowScratch*>(cum + kWinWords + 4);
+  unsigned char* tile = smem;                                                         // kTileBudget bytes
+  NumScratch<T>* ns = reinterpret_cast<NumScratch<T>*>(smem + kTileBudget);
   if (ctl->error) return;
   const bool sorted = ctl->b_sorted != 0;
-  const bool use_wp = sorted && wp != nullptr;
   const int tid = threadIdx.x;
-  bool flags_clean = false;
+  const unsigned nruns = ctl->run_cursor;
   while (true) {
-    const int row = next_dense_row(perm, ctl, 1, &rs->s_row);
-    if (row < 0) break;
-    const int64_t a0 = a_rp[row];
-    const int d = (int)(a_rp[row + 1] - a0);
-    int64_t out = c_rp[row];
-    for (int w_id = 0; w_id < nw; ++w_id) {
-      const int64_t c0 = (int64_t)w_id * kWinCols;
-      const int64_t c1 = (c0 + kWinCols < n_cols) ? c0 + kWinCols : n_cols;
-      const int words = (int)((c1 - c0 + 31) >> 5);
-      const int wlo_col = (int)c0, whi_col = (int)c1;
-      if (!flags_clean) {
-        for (int w = tid; w < kWinWords; w += kDenseThreads) flags[w] = 0;
-        flags_clean = true;
-      }
-      // (the barriers inside stream_products order the clearing before the first mark)
-      // pass 1: which columns of this window exist in the row
-      auto mark = [&](int c, double) {
-        if (c >= wlo_col && c < whi_col) atomicOr(&flags[(c - wlo_col) >> 5], 1u << ((c - wlo_col) & 31));
-      };
-      int visited;
-      if (use_wp)
-        visited = stream_products<false, T>(a0, d, a_col, a_val, b_rp, b_col, b_val, rs,
-                                            WindowRange{wp, b_col, nw + 1, w_id, wlo_col, whi_col, false}, mark);
-      else if (sorted)
-        visited = stream_products<false, T>(a0, d, a_col, a_val, b_rp, b_col, b_val, rs, SearchRange{b_col, wlo_col, whi_col}, mark);
-      else
-        visited = stream_products<false, T>(a0, d, a_col, a_val, b_rp, b_col, b_val, rs, NoRange{}, mark);
-      if (visited == 0) continue;   // nothing of this row falls into the window: flags still clear
-      flags_clean = false;
-      // exclusive prefix of the flag-word populations (consecutive words per thread)
-      constexpr int kPer = kWinWords / kDenseThreads;
-      int pc[kPer], mine = 0;
-#pragma unroll
-      for (int t = 0; t < kPer; ++t) { pc[t] = __popc(flags[tid * kPer + t]); mine += pc[t]; }
-      int excl, dummy_e, win_total, dummy_t;
-      block_excl_scan2(mine, 0, excl, dummy_e, win_total, dummy_t, rs->red);
-      int run = excl;
-#pragma unroll
-      for (int t = 0; t < kPer; ++t) { cum[tid * kPer + t] = (unsigned)run; run += pc[t]; }
-      if (tid == kDenseThreads - 1) cum[kWinWords] = (unsigned)run;
-      __syncthreads();
-      if (win_total == 0) continue;
-      // tiles: flag words whose prefix lies in [t*kTileCut, (t+1)*kTileCut)
-      for (int tile_lo = 0; tile_lo < win_total; tile_lo += kTileCut) {
-        int wa, wb;
-        {
-          int lo = 0, hi = kWinWords;   // first word with cum >= tile_lo
-          while (lo < hi) { const int mid = (lo + hi) >> 1; if ((int)cum[mid] < tile_lo) lo = mid + 1; else hi = mid; }
-          wa = lo;
-          hi = kWinWords;               // first word with cum >= tile_lo + kTileCut
-          while (lo < hi) { const int mid = (lo + hi) >> 1; if ((int)cum[mid] < tile_lo + kTileCut) lo = mid + 1; else hi = mid; }
-          wb = lo;
-        }
-        if (wb > words) wb = words;
-        const int base = (int)cum[wa];
-        const int count = (int)cum[wb] - base;
-        if (count <= 0) continue;
-        for (int r = tid; r < count; r += kDenseThreads) acc[r] = 0.0;
-        const int t_lo = wlo_col + wa * 32;
-        int t_hi = wlo_col + wb * 32;
-        if (t_hi > whi_col) t_hi = whi_col;
-        const bool whole = (wa == 0 && wb == words);
-        // pass 2: accumulate a_ik * b_kj at the rank of column j
-        auto add = [&](int c, double prod) {
-          if (c >= t_lo && c < t_hi) {
-            const int rel = c - wlo_col;
-            const int w = rel >> 5;
-            const int rank = (int)cum[w] - base + __popc(flags[w] & ((1u << (rel & 31)) - 1u));
-            __hip_atomic_fetch_add(&acc[rank], prod, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-          }
-        };
-        if (use_wp)
-          stream_products<true, T>(a0, d, a_col, a_val, b_rp, b_col, b_val, rs,
-                                   WindowRange{wp, b_col, nw + 1, w_id, t_lo, t_hi, !whole}, add);
-        else if (sorted)
-          stream_products<true, T>(a0, d, a_col, a_val, b_rp, b_col, b_val, rs, SearchRange{b_col, t_lo, t_hi}, add);
-        else
-          stream_products<true, T>(a0, d, a_col, a_val, b_rp, b_col, b_val, rs, NoRange{}, add);
-        // compress: values are already in column order; columns are decoded from the flags
-        for (int r = tid; r < count; r += kDenseThreads) c_val[out + r] = (T)acc[r];
-        for (int w = wa + tid; w < wb; w += kDenseThreads) {
-          unsigned bits = flags[w];
-          int64_t pos = out + ((int)cum[w] - base);
-          while (bits) {
-            const int b = __ffs((int)bits) - 1;
-            bits &= bits - 1;
-            c_col[pos++] = wlo_col + w * 32 + b;
-          }
-        }
-        out += count;
-        __syncthreads();
-      }
+    __syncthreads();
+    if (tid == 0) {
+      const unsigned r = atomicAdd(&ctl->work[1], 1u);
+      ns->s_run = r < nruns ? (int)r : -1;
     }
+    __syncthreads();
+    const int run = ns->s_run;
+    if (run < 0) break;
+    const RunRec rr = runs[run];
+    const int cls = numbin[rr.row];
+    const int64_t out_row = c_rp[rr.row];
+    if (tid < rr.count) ns->rec[tid] = tiles[rr.first + tid];
+    if (cls < 4 || cls > 6) continue;   // the row's numeric class is not this kernel's
+    __syncthreads();
+    if (sorted)
+      num_dense_run<T, false>(rr, ns, tile, true, a_col, a_val, b_rp, b_col, b_val, n_cols, bp, nb1, out_row, c_col, c_val);
+    else
+      num_dense_run<T, true>(rr, ns, tile, false, a_col, a_val, b_rp, b_col, b_val, n_cols, bp, nb1, out_row, c_col, c_val);
   }
 }
 
-constexpr size_t kNumDenseLds = (size_t)kTileSlots * 8 + (size_t)(2 * kWinWords + 4) * 4 + sizeof(RowScratch);
+template <typename T>
+constexpr size_t num_dense_lds() { return (size_t)kTileBudget + sizeof(NumScratch<T>); }
 
 }  // namespace spg

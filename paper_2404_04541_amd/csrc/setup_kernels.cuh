@@ -24,6 +24,7 @@ __global__ __launch_bounds__(256) void k_validate_b(int64_t rows, int64_t cols, 
   for (int64_t i = t0; i < rows; i += stride) {
     const int64_t a = rp[i], b = rp[i + 1];
     if (b < a || a < 0 || b > nnz || b - a > 0x7fffffff) { bad = true; continue; }
+    if (b - a >= (1 << 21)) ctl->long_b_row = 1;
     if (b > a && a > 0 && col[a] <= col[a - 1]) ++bnd;
   }
   for (int64_t p = t0; p < nnz; p += stride) {
@@ -149,7 +150,11 @@ __global__ void k_bin_offsets(Control* ctl, int phase) {
       ctl->cursor[phase][b] = 0;
     }
     ctl->offset[phase][kNumBins] = s;
-    if (phase == 0) ctl->b_sorted = (ctl->desc_flat == ctl->desc_bnd) ? 1 : 0;
+    if (phase == 0) {
+      ctl->b_sorted = (ctl->desc_flat == ctl->desc_bnd) ? 1 : 0;
+      // the dense workspaces walk whole rows of an unsorted B per tile: 32-bit piece prefixes
+      if (!ctl->b_sorted && ctl->long_b_row && !ctl->error) ctl->error = 2;
+    }
   }
 }
 

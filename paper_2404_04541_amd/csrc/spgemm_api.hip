@@ -29,6 +29,7 @@ struct spgemm_context {
   bool has_alloc = false;
   int timing = 0;
   int force = 0;
+  int direct_min = kDirectMinDefault;
   std::string err = "";
   bool device_ready = false;
   int num_cus = 0;
@@ -47,8 +48,11 @@ struct spgemm_plan_s {
   int* perm_num = nullptr;
   unsigned char* bin = nullptr;
   long long* partial = nullptr;
-  int* win_ptr = nullptr;   // rows(B) x (num_windows + 1) offsets, null when the table would be too large
-  int num_windows = 0;
+  void* scratch2 = nullptr;  // sized after the row classes are known: block offsets of B, tile and run lists
+  int* blk_ptr = nullptr;    // rows(B) x blk_ptr_cols offsets, null when not needed or too large
+  int blk_ptr_cols = 0;      // column blocks + 1
+  TileRec* tiles = nullptr;
+  RunRec* runs = nullptr;
   Control* ctl = nullptr;
   int64_t scan_blocks = 0;
   bool symbolic_done = false;
@@ -121,11 +125,8 @@ int ensure_device(spgemm_context* h) {
   h->num_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
   int rc;
   if ((rc = allow_lds(h, k_sym_dense, kSymDenseLds))) return rc;
-  if ((rc = allow_lds(h, k_num_dense<float>, kNumDenseLds))) return rc;
-  if ((rc = allow_lds(h, k_num_dense<double>, kNumDenseLds))) return rc;
-  const size_t big_hash = hash_lds_bytes<256, 14, false>();
-  if ((rc = allow_lds(h, k_hash<256, 14, float, false>, big_hash))) return rc;
-  if ((rc = allow_lds(h, k_hash<256, 14, double, false>, big_hash))) return rc;
+  if ((rc = allow_lds(h, k_num_dense<float>, num_dense_lds<float>()))) return rc;
+  if ((rc = allow_lds(h, k_num_dense<double>, num_dense_lds<double>()))) return rc;
   h->device_ready = true;
   return SPGEMM_OK;
 }
@@ -186,13 +187,11 @@ inline unsigned grid_for(int64_t items, int64_t per_block, int64_t cap) {
 
 size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
 
-template <typename T>
-int run_symbolic(spgemm_context* h, spgemm_plan_s* p, const spgemm_csr* A, const spgemm_csr* B, int64_t* c_rowptr) {
+// Symbolic phase, first part: count, check, bin.  Ends with the control block on the host
+// (one synchronisation): the second part sizes its lists and launches from the bin populations.
+int run_setup(spgemm_context* h, spgemm_plan_s* p, const spgemm_csr* A, const spgemm_csr* B, Control* host) {
   hipStream_t s = h->stream;
   const int64_t m = p->m;
-  const int64_t cap_small = (int64_t)h->num_cus * 32;
-  const size_t lds_hash_small = hash_lds_bytes<64, 11, false>();
-  const size_t lds_hash_large = hash_lds_bytes<256, 14, false>();
   {
     Timer t(h, SPGEMM_K_COUNT);
     hipLaunchKernelGGL(k_init_control, dim3(1), dim3(64), 0, s, p->ctl);
@@ -208,36 +207,104 @@ int run_symbolic(spgemm_context* h, spgemm_plan_s* p, const spgemm_csr* A, const
     if (m > 0)
       hipLaunchKernelGGL(k_bin_scatter, dim3((unsigned)ceil_div(m, 256)), dim3(256), 0, s, m, p->bin, p->perm_sym, p->ctl, 0);
   }
-  if (m > 0 && p->win_ptr) {
-    Timer t(h, SPGEMM_K_WINDOW_PTR);
-    const int64_t items = B->rows * (int64_t)(p->num_windows + 1);
-    hipLaunchKernelGGL(k_window_ptrs, dim3(grid_for(items, 256, (int64_t)h->num_cus * 32)), dim3(256), 0, s, B->rows,
-                       p->num_windows, B->rowptr, B->colidx, p->ctl, p->win_ptr);
+  HIP_TRY(h, hipGetLastError());
+  HIP_TRY(h, hipMemcpyAsync(host, p->ctl, sizeof(Control), hipMemcpyDeviceToHost, s));
+  HIP_TRY(h, hipStreamSynchronize(s));
+  return SPGEMM_OK;
+}
+
+// Sizes and allocates what the dense kernels need beyond the per-row arrays: the tile and run
+// lists (from an upper bound of the number of tiles) and the table of block offsets of B.
+int alloc_dense_lists(spgemm_context* h, spgemm_plan_s* p, const spgemm_csr* B, const Control& host, unsigned* tile_cap,
+                      unsigned* run_cap) {
+  *tile_cap = 0; *run_cap = 0;
+  double rows_d = 0, ip_d = 0;
+  for (int b = 4; b <= 6; ++b) { rows_d += host.hist[0][b]; ip_d += (double)host.bin_ip[0][b]; }
+  if (rows_d == 0) return SPGEMM_OK;
+  const double n = (double)B->cols;
+  const double blocks = (double)ceil_div(B->cols, kBlkCols);
+  const double spans = (double)ceil_div(B->cols, (int64_t)kSymFlagWords * 32);
+  // direct tiles hold at least direct_min entries each and there is at most one per block;
+  // of two neighbouring ranked tiles at least one pair exceeds the tile budget together
+  double direct = rows_d * blocks;
+  if (ip_d / h->direct_min < direct) direct = ip_d / h->direct_min;
+  const double entries = ip_d < rows_d * n ? ip_d : rows_d * n;
+  const double weight = rows_d * blocks * kRankBlkBytes + (double)kRankEntryBytes * entries;
+  const double tiles = 2.0 * direct + 2.0 * weight / kTileBudget + 4.0 * rows_d * spans + 16.0;
+  const double runs = tiles / kRunTiles + rows_d * spans + 16.0;
+  if (tiles > 4.0e9) return fail(h, SPGEMM_UNSUPPORTED, "tile list of the dense workspace would exceed 2^32 records");
+  *tile_cap = (unsigned)tiles;
+  *run_cap = (unsigned)runs;
+  p->blk_ptr_cols = (int)blocks + 1;
+  const size_t bp_bytes = (size_t)B->rows * (size_t)p->blk_ptr_cols * 4;
+  const bool with_bp = host.b_sorted && B->nnz > 0 && bp_bytes <= ((size_t)1 << 30);
+  size_t off = 0;
+  const size_t o_tiles = off; off = align_up(off + (size_t)*tile_cap * sizeof(TileRec));
+  const size_t o_runs = off; off = align_up(off + (size_t)*run_cap * sizeof(RunRec));
+  const size_t o_bp = off; if (with_bp) off = align_up(off + bp_bytes);
+  p->scratch2 = dev_alloc(h, off);
+  if (!p->scratch2) return fail(h, SPGEMM_ALLOC_FAILED, "device allocation of the dense workspace lists failed");
+  unsigned char* base = static_cast<unsigned char*>(p->scratch2);
+  p->tiles = reinterpret_cast<TileRec*>(base + o_tiles);
+  p->runs = reinterpret_cast<RunRec*>(base + o_runs);
+  p->blk_ptr = with_bp ? reinterpret_cast<int*>(base + o_bp) : nullptr;
+  return SPGEMM_OK;
+}
+
+__global__ void k_set_caps(Control* ctl, unsigned tile_cap, unsigned run_cap) {
+  if (threadIdx.x == 0) { ctl->tile_cap = tile_cap; ctl->run_cap = run_cap; }
+}
+
+template <typename T>
+int run_symbolic(spgemm_context* h, spgemm_plan_s* p, const spgemm_csr* A, const spgemm_csr* B, int64_t* c_rowptr,
+                 const Control& host) {
+  hipStream_t s = h->stream;
+  const int64_t m = p->m;
+  const int64_t cap_small = (int64_t)h->num_cus * 32;
+  const size_t lds_hash_small = hash_lds_bytes<64, 11, false>();
+  const size_t lds_hash_large = hash_lds_bytes<256, 12, false>();
+  const unsigned* hist = host.hist[0];
+  const int64_t rows_dense = (int64_t)hist[4] + hist[5] + hist[6];
+  unsigned tile_cap = 0, run_cap = 0;
+  int rc = alloc_dense_lists(h, p, B, host, &tile_cap, &run_cap);
+  if (rc) return rc;
+  if (rows_dense > 0) {
+    hipLaunchKernelGGL(k_set_caps, dim3(1), dim3(64), 0, s, p->ctl, tile_cap, run_cap);
+    if (p->blk_ptr) {
+      Timer t(h, SPGEMM_K_BLOCK_PTR);
+      const int64_t items = B->rows * (int64_t)p->blk_ptr_cols;
+      hipLaunchKernelGGL(k_block_ptrs, dim3(grid_for(items, 256, (int64_t)h->num_cus * 64)), dim3(256), 0, s, B->rows,
+                         p->blk_ptr_cols, B->rowptr, B->colidx, p->ctl, p->blk_ptr);
+    }
   }
   if (m > 0) {
     {
       Timer t(h, SPGEMM_K_SYM_ESC);
-      hipLaunchKernelGGL((k_esc<16, 32, T, false>), dim3(grid_for(m, 16, cap_small)), dim3(256), 0, s, p->perm_sym, p->ctl, 0, 0,
-                         A->rowptr, A->colidx, (const T*)nullptr, B->rowptr, B->colidx, (const T*)nullptr, p->cnt,
-                         (const int64_t*)nullptr, (int32_t*)nullptr, (T*)nullptr);
-      hipLaunchKernelGGL((k_esc<64, 128, T, false>), dim3(grid_for(m, 4, cap_small)), dim3(256), 0, s, p->perm_sym, p->ctl, 0, 1,
-                         A->rowptr, A->colidx, (const T*)nullptr, B->rowptr, B->colidx, (const T*)nullptr, p->cnt,
-                         (const int64_t*)nullptr, (int32_t*)nullptr, (T*)nullptr);
+      if (hist[0])
+        hipLaunchKernelGGL((k_esc<16, 32, T, false>), dim3(grid_for(hist[0], 16, cap_small)), dim3(256), 0, s, p->perm_sym, p->ctl, 0, 0,
+                           A->rowptr, A->colidx, (const T*)nullptr, B->rowptr, B->colidx, (const T*)nullptr, p->cnt,
+                           (const int64_t*)nullptr, (int32_t*)nullptr, (T*)nullptr);
+      if (hist[1])
+        hipLaunchKernelGGL((k_esc<64, 128, T, false>), dim3(grid_for(hist[1], 4, cap_small)), dim3(256), 0, s, p->perm_sym, p->ctl, 0, 1,
+                           A->rowptr, A->colidx, (const T*)nullptr, B->rowptr, B->colidx, (const T*)nullptr, p->cnt,
+                           (const int64_t*)nullptr, (int32_t*)nullptr, (T*)nullptr);
     }
     {
       Timer t(h, SPGEMM_K_SYM_HASH);
-      hipLaunchKernelGGL((k_hash<64, 11, T, false>), dim3(grid_for(m, 4, cap_small)), dim3(256), lds_hash_small, s,
-                         p->perm_sym, p->ctl, 0, 2, p->ip, A->rowptr, A->colidx, (const T*)nullptr, B->rowptr, B->colidx,
-                         (const T*)nullptr, p->cnt, (const int64_t*)nullptr, (int32_t*)nullptr, (T*)nullptr);
-      hipLaunchKernelGGL((k_hash<256, 14, T, false>), dim3(grid_for(m, 1, (int64_t)h->num_cus * 8)), dim3(256),
-                         lds_hash_large, s, p->perm_sym, p->ctl, 0, 3, p->ip, A->rowptr, A->colidx,
-                         (const T*)nullptr, B->rowptr, B->colidx, (const T*)nullptr, p->cnt, (const int64_t*)nullptr,
-                         (int32_t*)nullptr, (T*)nullptr);
+      if (hist[2])
+        hipLaunchKernelGGL((k_hash<64, 11, T, false>), dim3(grid_for(hist[2], 4, cap_small)), dim3(256), lds_hash_small, s,
+                           p->perm_sym, p->ctl, 0, 2, p->ip, A->rowptr, A->colidx, (const T*)nullptr, B->rowptr, B->colidx,
+                           (const T*)nullptr, p->cnt, (const int64_t*)nullptr, (int32_t*)nullptr, (T*)nullptr);
+      if (hist[3])
+        hipLaunchKernelGGL((k_hash<256, 12, T, false>), dim3(grid_for(hist[3], 1, (int64_t)h->num_cus * 8)), dim3(256),
+                           lds_hash_large, s, p->perm_sym, p->ctl, 0, 3, p->ip, A->rowptr, A->colidx,
+                           (const T*)nullptr, B->rowptr, B->colidx, (const T*)nullptr, p->cnt, (const int64_t*)nullptr,
+                           (int32_t*)nullptr, (T*)nullptr);
     }
-    {
+    if (rows_dense > 0) {
       Timer t(h, SPGEMM_K_SYM_DENSE);
-      hipLaunchKernelGGL(k_sym_dense, dim3(grid_for(m, 1, h->num_cus)), dim3(kDenseThreads), kSymDenseLds, s, p->perm_sym, p->ctl,
-                         A->rowptr, A->colidx, B->rowptr, B->colidx, B->cols, p->cnt);
+      hipLaunchKernelGGL(k_sym_dense, dim3(grid_for(rows_dense, 1, h->num_cus)), dim3(kDenseThreads), kSymDenseLds, s, p->perm_sym,
+                         p->ctl, A->rowptr, A->colidx, B->rowptr, B->colidx, B->cols, p->cnt, p->tiles, p->runs, h->direct_min);
     }
     {
       Timer t(h, SPGEMM_K_BIN);
@@ -275,28 +342,34 @@ int run_numeric(spgemm_context* h, spgemm_plan_s* p, const spgemm_csr* A, const 
   T* c_val = static_cast<T*>(c_val_v);
   const size_t lds_hash_small = hash_lds_bytes<64, 8, true>();
   const size_t lds_hash_large = hash_lds_bytes<256, 11, true>();
+  const int64_t* hist = p->stats.num_bin_rows;
   hipLaunchKernelGGL(k_reset_numeric_work, dim3(1), dim3(64), 0, s, p->ctl);
   {
     Timer t(h, SPGEMM_K_NUM_ESC);
-    hipLaunchKernelGGL((k_esc<16, 32, T, true>), dim3(grid_for(m, 16, cap_small)), dim3(256), 0, s, p->perm_num, p->ctl, 1, 0,
-                       A->rowptr, A->colidx, a_val, B->rowptr, B->colidx, b_val, (int*)nullptr, c_rp, c_col, c_val);
-    hipLaunchKernelGGL((k_esc<64, 128, T, true>), dim3(grid_for(m, 4, cap_small)), dim3(256), 0, s, p->perm_num, p->ctl, 1, 1,
-                       A->rowptr, A->colidx, a_val, B->rowptr, B->colidx, b_val, (int*)nullptr, c_rp, c_col, c_val);
+    if (hist[0])
+      hipLaunchKernelGGL((k_esc<16, 32, T, true>), dim3(grid_for(hist[0], 16, cap_small)), dim3(256), 0, s, p->perm_num, p->ctl, 1, 0,
+                         A->rowptr, A->colidx, a_val, B->rowptr, B->colidx, b_val, (int*)nullptr, c_rp, c_col, c_val);
+    if (hist[1])
+      hipLaunchKernelGGL((k_esc<64, 128, T, true>), dim3(grid_for(hist[1], 4, cap_small)), dim3(256), 0, s, p->perm_num, p->ctl, 1, 1,
+                         A->rowptr, A->colidx, a_val, B->rowptr, B->colidx, b_val, (int*)nullptr, c_rp, c_col, c_val);
   }
   {
     Timer t(h, SPGEMM_K_NUM_HASH);
-    hipLaunchKernelGGL((k_hash<64, 8, T, true>), dim3(grid_for(m, 4, cap_small)), dim3(256), lds_hash_small, s,
-                       p->perm_num, p->ctl, 1, 2, p->ip, A->rowptr, A->colidx, a_val, B->rowptr, B->colidx, b_val, (int*)nullptr,
-                       c_rp, c_col, c_val);
-    hipLaunchKernelGGL((k_hash<256, 11, T, true>), dim3(grid_for(m, 1, (int64_t)h->num_cus * 8)), dim3(256),
-                       lds_hash_large, s, p->perm_num, p->ctl, 1, 3, p->ip, A->rowptr, A->colidx, a_val, B->rowptr,
-                       B->colidx, b_val, (int*)nullptr, c_rp, c_col, c_val);
+    if (hist[2])
+      hipLaunchKernelGGL((k_hash<64, 8, T, true>), dim3(grid_for(hist[2], 4, cap_small)), dim3(256), lds_hash_small, s,
+                         p->perm_num, p->ctl, 1, 2, p->ip, A->rowptr, A->colidx, a_val, B->rowptr, B->colidx, b_val, (int*)nullptr,
+                         c_rp, c_col, c_val);
+    if (hist[3])
+      hipLaunchKernelGGL((k_hash<256, 11, T, true>), dim3(grid_for(hist[3], 1, (int64_t)h->num_cus * 8)), dim3(256),
+                         lds_hash_large, s, p->perm_num, p->ctl, 1, 3, p->ip, A->rowptr, A->colidx, a_val, B->rowptr,
+                         B->colidx, b_val, (int*)nullptr, c_rp, c_col, c_val);
   }
-  {
+  const int64_t rows_dense = hist[4] + hist[5] + hist[6];
+  if (rows_dense > 0) {
     Timer t(h, SPGEMM_K_NUM_DENSE);
-    hipLaunchKernelGGL(k_num_dense<T>, dim3(grid_for(m, 1, h->num_cus)), dim3(kDenseThreads), kNumDenseLds, s, p->perm_num, p->ctl,
-                       A->rowptr, A->colidx, a_val, B->rowptr, B->colidx, b_val, B->cols, p->win_ptr, p->num_windows, c_rp, c_col,
-                       c_val);
+    hipLaunchKernelGGL(k_num_dense<T>, dim3(grid_for(rows_dense, 1, h->num_cus)), dim3(kDenseThreads), num_dense_lds<T>(), s, p->ctl,
+                       p->bin, p->tiles, p->runs, A->colidx, a_val, B->rowptr, B->colidx, b_val, B->cols, p->blk_ptr,
+                       p->blk_ptr_cols, c_rp, c_col, c_val);
   }
   HIP_TRY(h, hipGetLastError());
   return SPGEMM_OK;
@@ -341,6 +414,10 @@ int spgemm_set_option(spgemm_handle h, int option, int64_t value) {
       if (value < 0 || value > 3) return fail(h, SPGEMM_INVALID_ARG, "workspace option takes 0..3");
       h->force = (int)value;
       return SPGEMM_OK;
+    case SPGEMM_OPT_DIRECT_MIN:
+      if (value < 1 || value > 0x3fffffff) return fail(h, SPGEMM_INVALID_ARG, "direct-tile threshold takes 1..2^30-1");
+      h->direct_min = (int)value;
+      return SPGEMM_OK;
     default:
       return fail(h, SPGEMM_INVALID_ARG, "unknown option");
   }
@@ -351,6 +428,7 @@ const char* spgemm_last_error(spgemm_handle h) { return h ? h->err.c_str() : "nu
 int spgemm_plan_destroy(spgemm_plan p) {
   if (!p) return SPGEMM_INVALID_ARG;
   dev_free(p->h, p->scratch);
+  dev_free(p->h, p->scratch2);
   delete p;
   return SPGEMM_OK;
 }
@@ -392,10 +470,6 @@ int spgemm_symbolic(spgemm_handle h, const spgemm_csr* A, const spgemm_csr* B, i
   const size_t o_pn = off; off = align_up(off + (size_t)m * 4);
   const size_t o_bin = off; off = align_up(off + (size_t)m);
   const size_t o_part = off; off = align_up(off + (size_t)(p->scan_blocks + 1) * 8);
-  p->num_windows = (int)ceil_div(B->cols, kWinCols);
-  const size_t wp_bytes = (size_t)B->rows * (size_t)(p->num_windows + 1) * 4;
-  const bool with_wp = m > 0 && B->nnz > 0 && wp_bytes <= ((size_t)1 << 30);
-  const size_t o_wp = off; if (with_wp) off = align_up(off + wp_bytes);
   p->scratch = dev_alloc(h, off);
   if (!p->scratch) {
     delete p;
@@ -409,11 +483,12 @@ int spgemm_symbolic(spgemm_handle h, const spgemm_csr* A, const spgemm_csr* B, i
   p->perm_num = reinterpret_cast<int*>(base + o_pn);
   p->bin = base + o_bin;
   p->partial = reinterpret_cast<long long*>(base + o_part);
-  p->win_ptr = with_wp ? reinterpret_cast<int*>(base + o_wp) : nullptr;
 
-  rc = (A->dtype == SPGEMM_F32) ? run_symbolic<float>(h, p, A, B, c_rowptr) : run_symbolic<double>(h, p, A, B, c_rowptr);
   Control host{};
-  if (rc == SPGEMM_OK) {
+  rc = run_setup(h, p, A, B, &host);
+  if (rc == SPGEMM_OK && !host.error)
+    rc = (A->dtype == SPGEMM_F32) ? run_symbolic<float>(h, p, A, B, c_rowptr, host) : run_symbolic<double>(h, p, A, B, c_rowptr, host);
+  if (rc == SPGEMM_OK && !host.error) {
     hipError_t e = hipMemcpyAsync(&host, p->ctl, sizeof(Control), hipMemcpyDeviceToHost, h->stream);
     if (e == hipSuccess) e = hipStreamSynchronize(h->stream);
     if (e != hipSuccess) rc = fail(h, SPGEMM_HIP_ERROR, std::string("symbolic phase: ") + hipGetErrorString(e));
@@ -426,6 +501,11 @@ int spgemm_symbolic(spgemm_handle h, const spgemm_csr* A, const spgemm_csr* B, i
   }
   std::memset(&p->stats, 0, sizeof(p->stats));
   collect_times(h, &p->stats);
+  if (host.error == 2 || host.error == 3) {
+    spgemm_plan_destroy(p);
+    return host.error == 2 ? fail(h, SPGEMM_UNSUPPORTED, "unsorted B with a row of 2^21 or more entries")
+                           : fail(h, SPGEMM_HIP_ERROR, "internal: tile list overflow in the dense symbolic kernel");
+  }
   if (host.error) {
     spgemm_plan_destroy(p);
     return fail(h, SPGEMM_INVALID_INPUT, "device-side input check failed (column out of range or rowptr not monotone)");
@@ -439,6 +519,9 @@ int spgemm_symbolic(spgemm_handle h, const spgemm_csr* A, const spgemm_csr* B, i
     p->stats.num_bin_ip[b] = (int64_t)host.bin_ip[1][b];
     p->stats.num_bin_nnz[b] = (int64_t)host.bin_nnz[b];
   }
+  p->stats.dense_tiles = host.tile_cursor;
+  p->stats.dense_direct_tiles = host.direct_tiles;
+  p->stats.dense_runs = host.run_cursor;
   p->symbolic_done = true;
   *nnz_c = host.nnz_c;
   *plan = p;

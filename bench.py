@@ -109,8 +109,8 @@ def main() -> int:
     eff_gbs = bytes_stream * args.steps / dt / 1e9
     # dominant kernel: numeric dense workspace.  Algorithmic bytes per launch = the gathered B
     # entries of its rows (column + value per intermediate product) + the C entries it writes.
-    dense_ip = sum(st["num_bin_ip"][4:7])
-    dense_nnz = sum(st["num_bin_nnz"][4:7])
+    dense_ip = sum(st["num_bin_ip"][5:7])
+    dense_nnz = sum(st["num_bin_nnz"][5:7])
     dense_bytes = dense_ip * (4 + v) + dense_nnz * (4 + v)
     dense_ms = per_kernel.get("num_dense", 0.0) / args.steps
     achieved = dense_bytes / (dense_ms * 1e-3) / 1e9 if dense_ms > 0 else 0.0

@@ -81,6 +81,7 @@ enum {
   SPGEMM_K_NUM_ESC,    /* numeric, sorted-list workspace (expand, sort, merge duplicates) */
   SPGEMM_K_NUM_HASH,   /* numeric, LDS hash workspace + sort */
   SPGEMM_K_NUM_DENSE,  /* numeric, LDS dense workspace over column tiles (direct or ranked) */
+  SPGEMM_K_NUM_STAGED, /* numeric, coordinate list staged in LDS, windowed counting sort + merge */
   SPGEMM_K_BLOCK_PTR,  /* per-B-row column-block offsets used by the dense numeric kernel */
   SPGEMM_NUM_KERNEL_CLASSES
 };
@@ -90,8 +91,10 @@ enum {
 typedef struct {
   int64_t ip_total;                     /* intermediate products, sum over rows */
   int64_t nnz_c;                        /* nonzeros of C */
-  int64_t sym_bin_rows[SPGEMM_NUM_BINS]; /* rows per symbolic bin (bin 7 = rows without products) */
-  int64_t num_bin_rows[SPGEMM_NUM_BINS]; /* rows per numeric bin (bin 7 = empty rows of C) */
+  /* bins: symbolic 0,1 sorted list; 2,3 hash; 4,5,6 dense; 7 rows without products.
+   *       numeric  0,1 sorted list; 2,3 hash; 4 staged list; 5,6 dense; 7 empty rows of C. */
+  int64_t sym_bin_rows[SPGEMM_NUM_BINS];
+  int64_t num_bin_rows[SPGEMM_NUM_BINS];
   int64_t sym_bin_ip[SPGEMM_NUM_BINS];   /* intermediate products per symbolic bin (rows beyond 2^31-1 products saturate) */
   int64_t num_bin_ip[SPGEMM_NUM_BINS];   /* intermediate products per numeric bin */
   int64_t num_bin_nnz[SPGEMM_NUM_BINS];  /* entries of C per numeric bin */
@@ -109,7 +112,7 @@ enum {
   SPGEMM_OPT_TIMING = 1,
   /* Route rows through one workspace kind wherever its capacity allows (rows beyond that
    * capacity keep their normal route): 0 = normal binning (default), 1 = sorted-list,
-   * 2 = hash, 3 = dense.  All routes compute the same function (the paper's table of
+   * 2 = hash, 3 = dense, 4 = staged coordinate list (numeric phase).  All routes compute the same function (the paper's table of
    * library algorithms, section 4.4); tests use this to compare them. */
   SPGEMM_OPT_FORCE_WORKSPACE = 2,
   /* Dense workspace tuning: a block of 8192 columns in which a row of C has at least this

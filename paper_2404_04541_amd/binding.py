@@ -18,10 +18,10 @@ LIB_PATH = os.path.join(_HERE, "libspgemm_gfx950.so")
 
 SPGEMM_F32, SPGEMM_F64 = 0, 1
 OPT_TIMING, OPT_FORCE_WORKSPACE, OPT_DIRECT_MIN = 1, 2, 3
-WORKSPACE_AUTO, WORKSPACE_SORTED_LIST, WORKSPACE_HASH, WORKSPACE_DENSE = 0, 1, 2, 3
-NUM_KERNEL_CLASSES = 10
+WORKSPACE_AUTO, WORKSPACE_SORTED_LIST, WORKSPACE_HASH, WORKSPACE_DENSE, WORKSPACE_STAGED = 0, 1, 2, 3, 4
+NUM_KERNEL_CLASSES = 11
 NUM_BINS = 8
-KERNEL_CLASS_NAMES = ("count", "bin", "sym_esc", "sym_hash", "sym_dense", "scan", "num_esc", "num_hash", "num_dense", "block_ptr")
+KERNEL_CLASS_NAMES = ("count", "bin", "sym_esc", "sym_hash", "sym_dense", "scan", "num_esc", "num_hash", "num_dense", "num_staged", "block_ptr")
 
 STATUS_NAMES = {0: "OK", -1: "INVALID_ARG", -2: "DIM_MISMATCH", -3: "DTYPE_MISMATCH", -4: "UNSUPPORTED",
                 -5: "ALLOC_FAILED", -6: "HIP_ERROR", -7: "BAD_STATE", -8: "INVALID_INPUT"}

@@ -58,14 +58,16 @@ __device__ __forceinline__ void group_sync() {
   if constexpr (GROUP <= kWave) wave_sync(); else __syncthreads();
 }
 
-// Inclusive scan over the wave (all 64 lanes must call).
+// Inclusive scan over the wave (all 64 lanes must call), on the DPP data path: four
+// shifted adds inside each row of 16 lanes, then the row totals are broadcast into the
+// following rows (row_bcast 15 and 31).
 __device__ __forceinline__ int wave_incl_scan(int v) {
-  const int l = lane_id();
-#pragma unroll
-  for (int d = 1; d < kWave; d <<= 1) {
-    int t = __shfl_up(v, d, kWave);
-    if (l >= d) v += t;
-  }
+  v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, true);   // row_shr:1
+  v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, true);   // row_shr:2
+  v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, true);   // row_shr:4
+  v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, true);   // row_shr:8
+  v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);  // row_bcast:15 into rows 1 and 3
+  v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);  // row_bcast:31 into rows 2 and 3
   return v;
 }
 
@@ -111,17 +113,21 @@ __device__ __forceinline__ int classify_symbolic(long long ip, int force) {
   return dense;
 }
 
-__device__ __forceinline__ int classify_numeric(long long ip, int cnt, int force) {
+// Numeric classes: 0/1 sorted list, 2/3 hash, 4 staged products (at most staged_cap of them,
+// 0 = class not available), 5/6 dense tiles.
+__device__ __forceinline__ int classify_numeric(long long ip, int cnt, int force, int staged_cap) {
   if (cnt <= 0) return kEmptyBin;
-  const int dense = ip <= kDenseMid ? 4 : (ip <= kDenseBig ? 5 : 6);
+  const int dense = ip <= kDenseBig ? 5 : 6;
+  const bool staged_ok = ip <= staged_cap;
   if (force == 3) return dense;
+  if (force == 4 && staged_ok) return 4;
   if (force != 2) {
     if (ip <= kEscSmallCap) return 0;
     if (ip <= kEscLargeCap) return 1;
   }
   if (cnt <= kNumHashSmall) return 2;
   if (cnt <= kNumHashLarge) return 3;
-  return dense;
+  return staged_ok ? 4 : dense;
 }
 
 // Bitonic sort of N (power of two) keys held in LDS by G cooperating threads

@@ -250,13 +250,17 @@ __device__ __forceinline__ int prev_bit128(unsigned long long lo, unsigned long 
 // A block with at least direct_min entries is a direct tile of its own; the blocks between
 // are grouped greedily into ranked tiles of at most kTileBudget bytes
 // (kRankBlkBytes per block + kRankEntryBytes per entry).  Records land in tp->rec, their number in tp->ntiles.
-__device__ __forceinline__ void plan_tiles(TilePlan* tp, int nb, int block0, int direct_min) {
+__device__ __forceinline__ void plan_tiles(TilePlan* tp, int nb, int block0, int direct_min, bool count_only) {
   const int l = lane_id();
   const int c0 = l < nb ? tp->blk_cnt[l] : 0;
   const int c1 = l + 64 < nb ? tp->blk_cnt[l + 64] : 0;
   const int i0 = wave_incl_scan(c0);
   const int t0 = __shfl(i0, 63, kWave);
   const int i1 = wave_incl_scan(c1);
+  if (count_only) {   // the row's numeric class needs no tiles
+    if (l == 63) { tp->row_out += t0 + i1; tp->ntiles = 0; }
+    return;
+  }
   tp->cum[l] = i0 - c0;
   tp->cum[l + 64] = t0 + i1 - c1;
   if (l == 63) tp->cum[128] = t0 + i1;
@@ -319,8 +323,9 @@ __device__ __forceinline__ int next_dense_row(const int* __restrict__ perm, Cont
 __global__ __launch_bounds__(kDenseThreads) void k_sym_dense(const int* __restrict__ perm, Control* ctl,
                                                              const int64_t* __restrict__ a_rp, const int32_t* __restrict__ a_col,
                                                              const int64_t* __restrict__ b_rp, const int32_t* __restrict__ b_col,
-                                                             int64_t n_cols, int* __restrict__ cnt,
-                                                             TileRec* __restrict__ tiles, RunRec* __restrict__ runs, int direct_min) {
+                                                             int64_t n_cols, const int* __restrict__ ip, int* __restrict__ cnt,
+                                                             TileRec* __restrict__ tiles, RunRec* __restrict__ runs, int direct_min,
+                                                             int no_tiles_ip) {
   extern __shared__ __align__(16) unsigned char smem[];
   unsigned* flags = reinterpret_cast<unsigned*>(smem);                               // kSymFlagWords
   RowScratch* rs = reinterpret_cast<RowScratch*>(smem + (size_t)kSymFlagWords * 4);
@@ -369,7 +374,7 @@ __global__ __launch_bounds__(kDenseThreads) void k_sym_dense(const int* __restri
         if ((tid & 7) == 0) tp->blk_cnt[tid >> 3] = local;
       }
       __syncthreads();
-      if (tid < kWave) plan_tiles(tp, nb, (int)(c0 >> kBlkShift), direct_min);
+      if (tid < kWave) plan_tiles(tp, nb, (int)(c0 >> kBlkShift), direct_min, ip[row] <= no_tiles_ip);
       __syncthreads();
       const int nt = tp->ntiles;
       const int nr = (nt + kRunTiles - 1) / kRunTiles;
@@ -535,6 +540,14 @@ __device__ __forceinline__ void num_dense_run(const RunRec rr, NumScratch<T>* ns
     my_rs = b_rp[my_k];
     my_re = b_rp[my_k + 1];
   }
+  const bool use_table = sorted && bp != nullptr;
+  int pf0 = 0, pf1 = 0;   // block offsets of the coming tile inside this thread's B row
+  if (use_table && nseg == 1 && tid < d) {
+    const TileRec nx = ns->rec[0];
+    const int* row = bp + (int64_t)my_k * nb1;
+    pf0 = row[nx.b0];
+    pf1 = row[nx.b1];
+  }
   for (int t = 0; t < rr.count; ++t) {
     const TileRec tr = ns->rec[t];
     const bool direct = (tr.cnt & kDirectBit) != 0;
@@ -546,7 +559,21 @@ __device__ __forceinline__ void num_dense_run(const RunRec rr, NumScratch<T>* ns
     // this thread's piece of the tile (one segment), or per segment below
     long long s = 0;
     int len = 0;
-    if (nseg == 1 && tid < d) piece_range(my_k, my_rs, my_re, tr.b0, tr.b1, t_lo, t_hi, sorted, bp, nb1, b_col, s, len);
+    if (nseg == 1 && tid < d) {
+      if (use_table) {
+        // offsets were fetched while the previous tile was in the works; fetch the next tile's now
+        s = my_rs + pf0;
+        len = pf1 - pf0;
+        if (t + 1 < rr.count) {
+          const TileRec nx = ns->rec[t + 1];
+          const int* row = bp + (int64_t)my_k * nb1;
+          pf0 = nx.b0 == tr.b1 ? pf1 : row[nx.b0];
+          pf1 = row[nx.b1];
+        }
+      } else {
+        piece_range(my_k, my_rs, my_re, tr.b0, tr.b1, t_lo, t_hi, sorted, bp, nb1, b_col, s, len);
+      }
+    }
     auto seg_piece = [&](int sg, long long& ps, int& plen, T& pav) {
       ps = 0; plen = 0; pav = T(0);
       const int e = sg * kSegCap + tid;
@@ -625,18 +652,31 @@ __device__ __forceinline__ void num_dense_run(const RunRec rr, NumScratch<T>* ns
         });
         if (nseg > 1) __syncthreads();
       }
-      // exclusive prefix of the flag-word populations (consecutive words per thread)
-      const int per = (nw + kDenseThreads - 1) / kDenseThreads;
-      const int w0 = tid * per;
+      // exclusive prefix of the flag-word populations: every wave owns a contiguous share of
+      // the words and walks it 64 words at a time (lane = word, so LDS reads do not collide)
+      const int wave = tid >> 6, lane = tid & 63;
+      const int wper = ((nw + kDenseThreads - 1) / kDenseThreads) * kWave;
+      const int wbase = wave * wper;
       __syncthreads();
       int mine = 0;
-      for (int w = w0; w < w0 + per && w < nw; ++w) mine += __popc(fc[w].x);
-      int excl, dummy_e, win_total, dummy_t;
-      block_excl_scan2(mine, 0, excl, dummy_e, win_total, dummy_t, ns->red);
-      (void)win_total;
-      for (int w = w0; w < w0 + per && w < nw; ++w) {
-        unsigned bits = fc[w].x;
-        fc[w].y = (unsigned)excl;
+      for (int i = lane; i < wper; i += kWave) {
+        const int w = wbase + i;
+        if (w < nw) mine += __popc(fc[w].x);
+      }
+      mine = wave_sum(mine);
+      if (lane == 0) ns->red[wave] = mine;
+      __syncthreads();
+      int running = 0;
+#pragma unroll
+      for (int w = 0; w < kDenseWaves; ++w) running += w < wave ? ns->red[w] : 0;
+      for (int i0 = 0; i0 < wper; i0 += kWave) {
+        const int w = wbase + i0 + lane;
+        unsigned bits = w < nw ? fc[w].x : 0u;
+        const int c = __popc(bits);
+        const int incl = wave_incl_scan(c);
+        int excl = running + incl - c;
+        running += __shfl(incl, kWave - 1, kWave);
+        if (w < nw) fc[w].y = (unsigned)excl;
         const int cbase = t_lo + w * 32;
         while (bits) {   // columns are decoded from the flag words ("boolean indexing")
           const int b = __ffs((int)bits) - 1;
@@ -702,7 +742,7 @@ __global__ __launch_bounds__(kDenseThreads) void k_num_dense(Control* ctl, const
     const int cls = numbin[rr.row];
     const int64_t out_row = c_rp[rr.row];
     if (tid < rr.count) ns->rec[tid] = tiles[rr.first + tid];
-    if (cls < 4 || cls > 6) continue;   // the row's numeric class is not this kernel's
+    if (cls < 5 || cls > 6) continue;   // the row's numeric class is not this kernel's
     __syncthreads();
     if (sorted)
       num_dense_run<T, false>(rr, ns, tile, true, a_col, a_val, b_rp, b_col, b_val, n_cols, bp, nb1, out_row, c_col, c_val);

@@ -118,14 +118,14 @@ __global__ __launch_bounds__(256) void k_count_rows(int64_t m, int64_t nnz_a, in
 
 // Numeric classes from ip and the symbolic counts.
 __global__ void k_classify_numeric(int64_t m, const int* __restrict__ ip, const int* __restrict__ cnt,
-                                   unsigned char* __restrict__ bin_out, Control* ctl, int force) {
+                                   unsigned char* __restrict__ bin_out, Control* ctl, int force, int staged_cap) {
   __shared__ unsigned hist[kNumBins];
   __shared__ unsigned long long hip[kNumBins], hnz[kNumBins];
   if (threadIdx.x < kNumBins) { hist[threadIdx.x] = 0; hip[threadIdx.x] = 0; hnz[threadIdx.x] = 0; }
   __syncthreads();
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < m; i += stride) {
-    const int bin = classify_numeric(ip[i], cnt[i], force);
+    const int bin = classify_numeric(ip[i], cnt[i], force, staged_cap);
     bin_out[i] = (unsigned char)bin;
     atomicAdd(&hist[bin], 1u);
     if (bin != kEmptyBin) {

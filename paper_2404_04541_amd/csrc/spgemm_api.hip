@@ -15,6 +15,7 @@
 #include "esc_kernels.cuh"
 #include "hash_kernels.cuh"
 #include "dense_kernels.cuh"
+#include "staged_kernels.cuh"
 
 using namespace spg;
 
@@ -127,6 +128,8 @@ int ensure_device(spgemm_context* h) {
   if ((rc = allow_lds(h, k_sym_dense, kSymDenseLds))) return rc;
   if ((rc = allow_lds(h, k_num_dense<float>, num_dense_lds<float>()))) return rc;
   if ((rc = allow_lds(h, k_num_dense<double>, num_dense_lds<double>()))) return rc;
+  if ((rc = allow_lds(h, k_num_staged<float>, staged_lds<float>()))) return rc;
+  if ((rc = allow_lds(h, k_num_staged<double>, staged_lds<double>()))) return rc;
   h->device_ready = true;
   return SPGEMM_OK;
 }
@@ -265,6 +268,8 @@ int run_symbolic(spgemm_context* h, spgemm_plan_s* p, const spgemm_csr* A, const
   const size_t lds_hash_large = hash_lds_bytes<256, 12, false>();
   const unsigned* hist = host.hist[0];
   const int64_t rows_dense = (int64_t)hist[4] + hist[5] + hist[6];
+  // rows of at most this many products never reach the dense numeric kernel (0: class unavailable)
+  const int staged = (h->force != 3 && ceil_div(B->cols, kStWinCols) <= kStMaxWindows) ? staged_cap<T>() : 0;
   unsigned tile_cap = 0, run_cap = 0;
   int rc = alloc_dense_lists(h, p, B, host, &tile_cap, &run_cap);
   if (rc) return rc;
@@ -304,12 +309,13 @@ int run_symbolic(spgemm_context* h, spgemm_plan_s* p, const spgemm_csr* A, const
     if (rows_dense > 0) {
       Timer t(h, SPGEMM_K_SYM_DENSE);
       hipLaunchKernelGGL(k_sym_dense, dim3(grid_for(rows_dense, 1, h->num_cus)), dim3(kDenseThreads), kSymDenseLds, s, p->perm_sym,
-                         p->ctl, A->rowptr, A->colidx, B->rowptr, B->colidx, B->cols, p->cnt, p->tiles, p->runs, h->direct_min);
+                         p->ctl, A->rowptr, A->colidx, B->rowptr, B->colidx, B->cols, p->ip, p->cnt, p->tiles, p->runs, h->direct_min,
+                         staged);
     }
     {
       Timer t(h, SPGEMM_K_BIN);
       hipLaunchKernelGGL(k_classify_numeric, dim3(grid_for(m, 256, (int64_t)h->num_cus * 8)), dim3(256), 0, s, m, p->ip, p->cnt,
-                         p->bin, p->ctl, h->force);
+                         p->bin, p->ctl, h->force, staged);
       hipLaunchKernelGGL(k_bin_offsets, dim3(1), dim3(64), 0, s, p->ctl, 1);
       hipLaunchKernelGGL(k_bin_scatter, dim3((unsigned)ceil_div(m, 256)), dim3(256), 0, s, m, p->bin, p->perm_num, p->ctl, 1);
     }
@@ -327,7 +333,7 @@ int run_symbolic(spgemm_context* h, spgemm_plan_s* p, const spgemm_csr* A, const
 }
 
 __global__ void k_reset_numeric_work(Control* ctl) {
-  if (threadIdx.x == 0) ctl->work[1] = 0;
+  if (threadIdx.x == 0) { ctl->work[1] = 0; ctl->work[2] = 0; }
 }
 
 template <typename T>
@@ -364,7 +370,12 @@ int run_numeric(spgemm_context* h, spgemm_plan_s* p, const spgemm_csr* A, const 
                          lds_hash_large, s, p->perm_num, p->ctl, 1, 3, p->ip, A->rowptr, A->colidx, a_val, B->rowptr,
                          B->colidx, b_val, (int*)nullptr, c_rp, c_col, c_val);
   }
-  const int64_t rows_dense = hist[4] + hist[5] + hist[6];
+  if (hist[4]) {
+    Timer t(h, SPGEMM_K_NUM_STAGED);
+    hipLaunchKernelGGL(k_num_staged<T>, dim3(grid_for(hist[4], 1, h->num_cus)), dim3(kDenseThreads), staged_lds<T>(), s, p->perm_num,
+                       p->ctl, A->rowptr, A->colidx, a_val, B->rowptr, B->colidx, b_val, B->cols, c_rp, c_col, c_val);
+  }
+  const int64_t rows_dense = hist[5] + hist[6];
   if (rows_dense > 0) {
     Timer t(h, SPGEMM_K_NUM_DENSE);
     hipLaunchKernelGGL(k_num_dense<T>, dim3(grid_for(rows_dense, 1, h->num_cus)), dim3(kDenseThreads), num_dense_lds<T>(), s, p->ctl,
@@ -411,7 +422,7 @@ int spgemm_set_option(spgemm_handle h, int option, int64_t value) {
       h->timing = (int)value;
       return SPGEMM_OK;
     case SPGEMM_OPT_FORCE_WORKSPACE:
-      if (value < 0 || value > 3) return fail(h, SPGEMM_INVALID_ARG, "workspace option takes 0..3");
+      if (value < 0 || value > 4) return fail(h, SPGEMM_INVALID_ARG, "workspace option takes 0..4");
       h->force = (int)value;
       return SPGEMM_OK;
     case SPGEMM_OPT_DIRECT_MIN:
@@ -439,7 +450,7 @@ int spgemm_get_stats(spgemm_plan p, spgemm_stats* out) {
   if (p->numeric_pending) {
     spgemm_context* h = p->h;
     if (!h->timed.empty()) HIP_TRY(h, hipEventSynchronize(h->timed.back().stop));
-    for (int c = SPGEMM_K_NUM_ESC; c <= SPGEMM_K_NUM_DENSE; ++c) { p->stats.kernel_ms[c] = 0; p->stats.kernel_launches[c] = 0; }
+    for (int c = SPGEMM_K_NUM_ESC; c <= SPGEMM_K_NUM_STAGED; ++c) { p->stats.kernel_ms[c] = 0; p->stats.kernel_launches[c] = 0; }
     collect_times(h, &p->stats);
     p->numeric_pending = false;
   }

@@ -8,7 +8,7 @@ from helpers import gpu_product, assert_matches_oracle
 
 pytestmark = pytest.mark.gpu
 
-AUTO, LIST, HASH, DENSE = 0, 1, 2, 3
+AUTO, LIST, HASH, DENSE, STAGED = 0, 1, 2, 3, 4
 
 
 def run(A, B, force=AUTO, what="", via="phases"):
@@ -27,7 +27,7 @@ def test_config1_random_1000():
     assert st["sym_bin_rows"][1] == 1000  # ip = 100 per row: the one-wave sorted-list bin
 
 
-@pytest.mark.parametrize("force", [AUTO, LIST, HASH, DENSE])
+@pytest.mark.parametrize("force", [AUTO, LIST, HASH, DENSE, STAGED])
 def test_every_workspace_computes_the_same_function(force):
     # ragged rows from empty to a few thousand products: crosses every bin boundary
     A = W.random_csr(3000, 2500, 12, 5)
@@ -48,12 +48,13 @@ def test_stencil_small_grid():
     assert st["ip_total"] == (9 * 12 - 10) ** 3 and st["nnz_c"] == (5 * 12 - 6) ** 3
 
 
-@pytest.mark.parametrize("force", [AUTO, DENSE])
+@pytest.mark.parametrize("force", [AUTO, DENSE, STAGED])
 def test_rmat_small_scale_power_law(force):
     a, b = W.config3(scale=13)
     st = run(a, b, force, what=f"rmat scale 13 force={force}")
     if force == AUTO:
-        assert sum(st["num_bin_rows"][4:7]) > 0, "long rows must reach the dense workspace"
+        assert st["num_bin_rows"][4] > 0, "mid rows must reach the staged coordinate list"
+        assert sum(st["num_bin_rows"][5:7]) > 0, "long rows must reach the dense workspace"
 
 
 def test_rectangular_and_ttm_small():
@@ -70,13 +71,13 @@ def test_dense_workspace_many_windows_and_tiles():
     run(A, B, DENSE, what="dense windows")
     B2 = W.random_csr(3000, 40000, 400, 13)
     st = run(A, B2, AUTO, what="dense tiles")
-    assert sum(st["num_bin_rows"][4:7]) > 0
+    assert sum(st["num_bin_rows"][5:7]) > 0
 
 
 def test_unsorted_and_duplicate_inputs():
     A = W.random_csr(400, 300, 9, 21, sort_rows=False, allow_duplicates=True)
     B = W.random_csr(300, 500, 14, 22, sort_rows=False, allow_duplicates=True)
-    for force in (AUTO, HASH, DENSE):
+    for force in (AUTO, HASH, DENSE, STAGED):
         run(A, B, force, what=f"unsorted/duplicates force={force}")
 
 

@@ -117,9 +117,13 @@ enum {
   SPGEMM_OPT_FORCE_WORKSPACE = 2,
   /* Dense workspace tuning: a block of 8192 columns in which a row of C has at least this
    * many entries is accumulated in a dense array indexed by column (one pass over the
-   * products); sparser blocks are grouped and accumulated by rank (two passes).  Default 2048.
+   * products); sparser blocks are grouped and accumulated by rank.  256 or more; default 4096.
    * Applies to the next spgemm_symbolic on the handle. */
-  SPGEMM_OPT_DIRECT_MIN = 3
+  SPGEMM_OPT_DIRECT_MIN = 3,
+  /* 1 (default): the plan keeps the column indices of the dense workspace's ranked tiles
+   * (up to a third of the free device memory), which saves the numeric phase one pass over
+   * those tiles' products; rows that do not fit fall back to the two-pass route.  0: never. */
+  SPGEMM_OPT_COLUMN_LIST = 4
 };
 
 /* Create a handle bound to a HIP stream (hipStream_t passed as void*, null = default

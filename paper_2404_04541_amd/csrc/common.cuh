@@ -34,6 +34,7 @@ struct Control {
   unsigned tile_cursor, run_cursor;   // tile / run records written by the dense symbolic kernel
   unsigned tile_cap, run_cap;         // capacity of the two lists (set by the host)
   unsigned direct_tiles;              // how many of the tiles are direct
+  unsigned long long list_cursor, list_cap;   // entries used / available in the plan's column list
   int error;                      // nonzero: a device-side input check failed
   int b_sorted;                   // 1 when every B row is strictly ascending
   int long_b_row;                 // 1 when some B row has 2^21 or more entries

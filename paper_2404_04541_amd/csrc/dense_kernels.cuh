@@ -34,13 +34,20 @@ constexpr int kSpanBlocks = kSymFlagWords * 32 / kBlkCols;   // 128 blocks per s
 constexpr int kTileBudget = 135 * 1024; // LDS bytes of one numeric tile (flags + ranks + sums + columns)
 constexpr int kRankBlkBytes = kBlkCols / 32 * 8;   // flag word + rank per 32 columns of a ranked tile
 constexpr int kRankEntryBytes = 12;               // sum + column per entry of a ranked tile
-constexpr int kDirectMinDefault = 2048; // a block with at least this many entries becomes a direct tile
+constexpr int kDirectMinDefault = 4096; // a block with at least this many entries becomes a direct tile
 constexpr int kRunTiles = 16;           // tiles handed to a workgroup at a time
 constexpr int kDirectBit = 1 << 30;     // in TileRec::cnt
 constexpr int kSegCap = 1024;           // A entries described in LDS at a time (numeric)
+constexpr int kBlkWords = kBlkCols / 32;
+constexpr int kListStage = 320;          // entries that a wave gathers in LDS before writing them to the column list
+constexpr int kListBatch = 6;           // column-list loads in flight per thread
+constexpr int kRegSegs = 4;             // segments of A entries that the numeric kernel keeps in registers
+constexpr long long kListBias = 1LL << 40;   // RunRec::list holds position + bias (so that -1 can mean "none")
 
 struct TileRec { int b0, b1, cnt, out; };     // blocks [b0, b1), entries (| kDirectBit), offset inside the row of C
-struct RunRec { int row; unsigned first; int count, d; long long a0, pad; };   // tiles [first, first + count) of one row; its A entries [a0, a0 + d)
+// tiles [first, first + count) of one row; its A entries [a0, a0 + d); list: where entry 0 of the
+// row sits in the column list, plus kListBias (-1: the row has no list)
+struct RunRec { int row; unsigned first; int count, d; long long a0, list; };
 
 // Per-workgroup bookkeeping of the piece walker below.
 struct RowScratch {
@@ -219,6 +226,8 @@ struct TilePlan {
   int ntiles, ndirect;
   unsigned tile_base, run_base;
   int row_out;
+  int span_out0;          // row_out when the span began
+  long long list_base;    // position of the span's first entry in the column list, -1 = none
 };
 
 // index of the lowest set bit at or above position b in the 128-bit mask (hi:lo); 128 when none
@@ -250,23 +259,38 @@ __device__ __forceinline__ int prev_bit128(unsigned long long lo, unsigned long 
 // A block with at least direct_min entries is a direct tile of its own; the blocks between
 // are grouped greedily into ranked tiles of at most kTileBudget bytes
 // (kRankBlkBytes per block + kRankEntryBytes per entry).  Records land in tp->rec, their number in tp->ntiles.
-__device__ __forceinline__ void plan_tiles(TilePlan* tp, int nb, int block0, int direct_min, bool count_only) {
+// First part (wave 0): entry prefix over the blocks, the span's total, and room in the plan's
+// column list for the span's entries (without room the numeric kernel rebuilds the flags itself).
+__device__ __forceinline__ void plan_head(TilePlan* tp, Control* ctl, int nb, bool count_only) {
   const int l = lane_id();
   const int c0 = l < nb ? tp->blk_cnt[l] : 0;
   const int c1 = l + 64 < nb ? tp->blk_cnt[l + 64] : 0;
   const int i0 = wave_incl_scan(c0);
   const int t0 = __shfl(i0, 63, kWave);
   const int i1 = wave_incl_scan(c1);
-  if (count_only) {   // the row's numeric class needs no tiles
-    if (l == 63) { tp->row_out += t0 + i1; tp->ntiles = 0; }
-    return;
-  }
   tp->cum[l] = i0 - c0;
   tp->cum[l + 64] = t0 + i1 - c1;
-  if (l == 63) tp->cum[128] = t0 + i1;
+  if (l == 63) {
+    const int total = t0 + i1;
+    tp->cum[128] = total;
+    tp->ntiles = 0;
+    tp->ndirect = 0;
+    if (count_only) {   // the row's numeric class needs no tiles
+      tp->row_out += total;
+    } else if (total > 0 && ctl->list_cap > 0) {
+      const unsigned long long at = atomicAdd(&ctl->list_cursor, (unsigned long long)total);
+      if (at + (unsigned long long)total <= ctl->list_cap) tp->list_base = (long long)at;
+    }
+  }
+}
+
+// Second part (wave 0): the tile records.
+__device__ __forceinline__ void plan_tail(TilePlan* tp, int nb, int block0, int direct_min) {
+  const int l = lane_id();
+  const int c0 = l < nb ? tp->blk_cnt[l] : 0;
+  const int c1 = l + 64 < nb ? tp->blk_cnt[l + 64] : 0;
   const unsigned long long dm0 = __ballot(c0 >= direct_min), dm1 = __ballot(c1 >= direct_min);
   const unsigned long long nm0 = __ballot(c0 > 0), nm1 = __ballot(c1 > 0);
-  wave_sync();
 #pragma unroll
   for (int half = 0; half < 2; ++half) {
     const int b = l + 64 * half;
@@ -284,12 +308,13 @@ __device__ __forceinline__ void plan_tiles(TilePlan* tp, int nb, int block0, int
   }
   wave_sync();
   if (l == 0) {
-    int n = 0, out = tp->row_out;
+    int n = 0, nd = 0, out = tp->row_out;
     int b = next_bit128(nm0, nm1, 0);
     while (b < nb) {
       const int cb = tp->blk_cnt[b];
       if (cb >= direct_min) {
         tp->rec[n++] = TileRec{block0 + b, block0 + b + 1, cb | kDirectBit, out};
+        ++nd;
         out += cb;
         b = b + 1;
       } else {
@@ -303,7 +328,7 @@ __device__ __forceinline__ void plan_tiles(TilePlan* tp, int nb, int block0, int
       b = next_bit128(nm0, nm1, b);
     }
     tp->ntiles = n;
-    tp->ndirect = __popcll(dm0) + __popcll(dm1);
+    tp->ndirect = nd;
     tp->row_out = out;
   }
 }
@@ -324,8 +349,8 @@ __global__ __launch_bounds__(kDenseThreads) void k_sym_dense(const int* __restri
                                                              const int64_t* __restrict__ a_rp, const int32_t* __restrict__ a_col,
                                                              const int64_t* __restrict__ b_rp, const int32_t* __restrict__ b_col,
                                                              int64_t n_cols, const int* __restrict__ ip, int* __restrict__ cnt,
-                                                             TileRec* __restrict__ tiles, RunRec* __restrict__ runs, int direct_min,
-                                                             int no_tiles_ip) {
+                                                             TileRec* __restrict__ tiles, RunRec* __restrict__ runs,
+                                                             int32_t* __restrict__ col_list, int direct_min, int no_tiles_ip) {
   extern __shared__ __align__(16) unsigned char smem[];
   unsigned* flags = reinterpret_cast<unsigned*>(smem);                               // kSymFlagWords
   RowScratch* rs = reinterpret_cast<RowScratch*>(smem + (size_t)kSymFlagWords * 4);
@@ -349,6 +374,7 @@ __global__ __launch_bounds__(kDenseThreads) void k_sym_dense(const int* __restri
         for (int w = tid; w < kSymFlagWords / 4; w += kDenseThreads) f4[w] = make_uint4(0, 0, 0, 0);
       }
       if (tid < kSpanBlocks) tp->blk_cnt[tid] = 0;
+      if (tid == 0) { tp->span_out0 = tp->row_out; tp->list_base = -1; }
       __syncthreads();
       const int lo = (int)c0;
       const int64_t hi = c1;
@@ -374,7 +400,61 @@ __global__ __launch_bounds__(kDenseThreads) void k_sym_dense(const int* __restri
         if ((tid & 7) == 0) tp->blk_cnt[tid >> 3] = local;
       }
       __syncthreads();
-      if (tid < kWave) plan_tiles(tp, nb, (int)(c0 >> kBlkShift), direct_min, ip[row] <= no_tiles_ip);
+      const bool count_only = ip[row] <= no_tiles_ip;
+      if (tid < kWave) plan_head(tp, ctl, nb, count_only);
+      __syncthreads();
+      const long long lb = tp->list_base;
+      if (!count_only) {
+        // wave 0 cuts the tiles while the other waves already write the column list
+        if (tid < kWave) plan_tail(tp, nb, (int)(c0 >> kBlkShift), direct_min);
+        if (lb >= 0) {
+          // wave v owns flag words [2048 v, 2048 v + 2048), i.e. blocks 8 v .. 8 v + 7; the list position
+          // of a block's first entry is its entry prefix.  Sparse blocks: the columns are decoded, a round
+          // of 64 words with few entries is gathered in LDS first and leaves as one coalesced run.
+          // Direct blocks: the numeric kernel wants the flag words themselves (their 256 words fit
+          // in the space of the block's entries).
+          const int wave = tid >> 6, lane = tid & 63;
+          int* wst = reinterpret_cast<int*>(rs) + wave * kListStage;   // the piece walker's scratch is free now
+          for (int bl = 0; bl < kSpanBlocks / kDenseWaves; ++bl) {
+            const int blk = wave * (kSpanBlocks / kDenseWaves) + bl;
+            const int cb = tp->blk_cnt[blk];
+            if (cb == 0) continue;
+            int running = tp->cum[blk];
+            if (cb >= direct_min) {
+#pragma unroll
+              for (int q = 0; q < kBlkWords; q += kWave) col_list[lb + running + q + lane] = (int)flags[blk * kBlkWords + q + lane];
+              continue;
+            }
+            for (int q = 0; q < kBlkWords; q += kWave) {
+              const int w = blk * kBlkWords + q + lane;
+              unsigned bits = flags[w];
+              const int c = __popc(bits);
+              const int incl = wave_incl_scan(c);
+              const int tot = __shfl(incl, kWave - 1, kWave);
+              if (tot == 0) continue;
+              int excl = incl - c;
+              const int cbase = lo + w * 32;
+              if (tot <= kListStage) {
+                while (bits) {
+                  const int b = __ffs((int)bits) - 1;
+                  bits &= bits - 1;
+                  wst[excl++] = cbase + b;
+                }
+                wave_sync();
+                for (int j = lane; j < tot; j += kWave) col_list[lb + running + j] = wst[j];
+                wave_sync();
+              } else {
+                while (bits) {
+                  const int b = __ffs((int)bits) - 1;
+                  bits &= bits - 1;
+                  col_list[lb + running + excl++] = cbase + b;
+                }
+              }
+              running += tot;
+            }
+          }
+        }
+      }
       __syncthreads();
       const int nt = tp->ntiles;
       const int nr = (nt + kRunTiles - 1) / kRunTiles;
@@ -392,7 +472,8 @@ __global__ __launch_bounds__(kDenseThreads) void k_sym_dense(const int* __restri
         if (tid < nt) tiles[tp->tile_base + tid] = tp->rec[tid];
         if (tid < nr) {
           const int left = nt - tid * kRunTiles;
-          runs[tp->run_base + tid] = RunRec{row, tp->tile_base + (unsigned)(tid * kRunTiles), left < kRunTiles ? left : kRunTiles, d, a0, 0};
+          runs[tp->run_base + tid] = RunRec{row, tp->tile_base + (unsigned)(tid * kRunTiles), left < kRunTiles ? left : kRunTiles, d, a0,
+                                            lb < 0 ? -1LL : lb - tp->span_out0 + kListBias};
         }
       }
       __syncthreads();
@@ -418,7 +499,7 @@ struct NumScratch {
   int pad;
 };
 
-constexpr int kChunkUnroll = 8;
+constexpr int kChunkUnroll = 12;
 
 __device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
 __device__ __forceinline__ long long uni64(long long v) {
@@ -427,11 +508,22 @@ __device__ __forceinline__ long long uni64(long long v) {
   return (long long)(((unsigned long long)hi << 32) | lo);
 }
 
+__device__ __forceinline__ int lane_get(int v, int lane) { return __builtin_amdgcn_readlane(v, lane); }
+__device__ __forceinline__ long long lane_get(long long v, int lane) {
+  const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(unsigned long long)v, lane);
+  const unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)((unsigned long long)v >> 32), lane);
+  return (long long)(((unsigned long long)hi << 32) | lo);
+}
+__device__ __forceinline__ float lane_get(float v, int lane) { return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane)); }
+__device__ __forceinline__ double lane_get(double v, int lane) { return __longlong_as_double(lane_get(__double_as_longlong(v), lane)); }
+
 // Visits every element of the pieces once.  A piece is cut into chunks of 64 elements; the
 // chunks of all pieces are dealt to the waves in contiguous shares; a wave reads a chunk
-// coalesced (one element per lane) with kChunkUnroll chunks in flight, and everything that
-// describes a chunk is wave-uniform.  f(column, a, b) is called per element (a, b only
-// meaningful when WITH_VALUES).
+// coalesced (one element per lane) with kChunkUnroll chunks in flight.  Everything that
+// describes a chunk is wave-uniform: the descriptors of the pieces that a batch of chunks can
+// touch are fetched from LDS by one lane each and handed out with readlane, so a batch costs
+// one LDS round trip before its loads are issued.  f(column, a, b) is called per element
+// (a, b only meaningful when WITH_VALUES).
 template <bool WITH_VALUES, typename T, class F>
 __device__ __forceinline__ void chunk_pass(int np, int nchunks, const NumScratch<T>* ns, const int32_t* __restrict__ b_col,
                                            const T* __restrict__ b_val, F f) {
@@ -451,11 +543,15 @@ __device__ __forceinline__ void chunk_pass(int np, int nchunks, const NumScratch
     }
     p = lo;
   }
-  int cfirst = uni(ns->c_cpre[p]), cnext = uni(ns->c_cpre[p + 1]);
-  int len = uni(ns->c_len[p]);
-  long long s = uni64(ns->c_s[p]);
-  T av = WITH_VALUES ? ns->c_av[p] : T(0);
   for (; c < cend; c += kChunkUnroll) {
+    // lane i describes piece p + i (a batch of kChunkUnroll chunks touches at most that many pieces)
+    const int pi = p + lane < np ? p + lane : np;
+    const int pj = p + lane < np ? p + lane : np - 1;
+    const int d_first = ns->c_cpre[pi];
+    const int d_len = ns->c_len[pj];
+    const long long d_s = ns->c_s[pj];
+    const T d_av = WITH_VALUES ? ns->c_av[pj] : T(0);
+    int q = 0;
     int col[kChunkUnroll];
     T bv[kChunkUnroll], au[kChunkUnroll];
 #pragma unroll
@@ -463,24 +559,19 @@ __device__ __forceinline__ void chunk_pass(int np, int nchunks, const NumScratch
       const int cu = c + u;
       col[u] = -1;
       bv[u] = T(0);
-      au[u] = av;
+      au[u] = T(0);
       if (cu < cend) {
-        if (cu >= cnext) {   // every piece has at least one chunk: one step suffices
-          ++p;
-          cfirst = cnext;
-          cnext = uni(ns->c_cpre[p + 1]);
-          len = uni(ns->c_len[p]);
-          s = uni64(ns->c_s[p]);
-          if (WITH_VALUES) av = ns->c_av[p];
-        }
-        const int off = (cu - cfirst) * kWave + lane;
-        if (off < len) {
+        if (cu >= lane_get(d_first, q + 1)) ++q;   // every piece has at least one chunk: one step suffices
+        const int off = (cu - lane_get(d_first, q)) * kWave + lane;
+        const long long s = lane_get(d_s, q);
+        if (off < lane_get(d_len, q)) {
           col[u] = b_col[s + off];
           if (WITH_VALUES) bv[u] = b_val[s + off];
         }
-        au[u] = av;
+        if (WITH_VALUES) au[u] = lane_get(d_av, q);
       }
     }
+    p += q;
 #pragma unroll
     for (int u = 0; u < kChunkUnroll; ++u)
       if (col[u] >= 0) f(col[u], au[u], bv[u]);
@@ -525,28 +616,39 @@ __device__ __forceinline__ void num_dense_run(const RunRec rr, NumScratch<T>* ns
                                               const int32_t* __restrict__ a_col, const T* __restrict__ a_val,
                                               const int64_t* __restrict__ b_rp, const int32_t* __restrict__ b_col,
                                               const T* __restrict__ b_val, int64_t n_cols, const int* __restrict__ bp, int nb1,
+                                              const int32_t* __restrict__ col_list,
                                               int64_t out_row, int32_t* __restrict__ c_col, T* __restrict__ c_val) {
   const int tid = threadIdx.x;
+  const bool have_list = rr.list >= 0;
+  const long long list_at = rr.list - kListBias;
   const int64_t a0 = rr.a0;
   const int d = rr.d;
   const int nseg = (d + kSegCap - 1) / kSegCap;
-  // with one segment, thread e keeps A entry e in registers for the whole run
-  int my_k = 0;
-  long long my_rs = 0, my_re = 0;
-  T my_av = T(0);
-  if (nseg == 1 && tid < d) {
-    my_k = a_col[a0 + tid];
-    my_av = a_val[a0 + tid];
-    my_rs = b_rp[my_k];
-    my_re = b_rp[my_k + 1];
-  }
+  // with few segments, thread e keeps its A entry of every segment in registers for the whole
+  // run, together with the block offsets of the coming tile inside the entry's B row (fetched
+  // while the current tile is in the works)
   const bool use_table = sorted && bp != nullptr;
-  int pf0 = 0, pf1 = 0;   // block offsets of the coming tile inside this thread's B row
-  if (use_table && nseg == 1 && tid < d) {
-    const TileRec nx = ns->rec[0];
-    const int* row = bp + (int64_t)my_k * nb1;
-    pf0 = row[nx.b0];
-    pf1 = row[nx.b1];
+  const bool cached = nseg == 1 || (use_table && nseg <= kRegSegs);
+  int ck[kRegSegs], pf0[kRegSegs], pf1[kRegSegs];
+  long long crs[kRegSegs];
+  T cav[kRegSegs];
+  long long my_re = 0;
+#pragma unroll
+  for (int g = 0; g < kRegSegs; ++g) {
+    ck[g] = 0; pf0[g] = 0; pf1[g] = 0; crs[g] = 0; cav[g] = T(0);
+    const int e = g * kSegCap + tid;
+    if (cached && e < d) {
+      ck[g] = a_col[a0 + e];
+      cav[g] = a_val[a0 + e];
+      crs[g] = b_rp[ck[g]];
+      if (!use_table) my_re = b_rp[ck[g] + 1];
+      if (use_table) {
+        const TileRec nx = ns->rec[0];
+        const int* row = bp + (int64_t)ck[g] * nb1;
+        pf0[g] = row[nx.b0];
+        pf1[g] = row[nx.b1];
+      }
+    }
   }
   for (int t = 0; t < rr.count; ++t) {
     const TileRec tr = ns->rec[t];
@@ -556,25 +658,39 @@ __device__ __forceinline__ void num_dense_run(const RunRec rr, NumScratch<T>* ns
     int64_t t_hi = (int64_t)tr.b1 << kBlkShift;
     if (t_hi > n_cols) t_hi = n_cols;
     const int64_t out = out_row + tr.out;
-    // this thread's piece of the tile (one segment), or per segment below
-    long long s = 0;
-    int len = 0;
-    if (nseg == 1 && tid < d) {
-      if (use_table) {
-        // offsets were fetched while the previous tile was in the works; fetch the next tile's now
-        s = my_rs + pf0;
-        len = pf1 - pf0;
-        if (t + 1 < rr.count) {
-          const TileRec nx = ns->rec[t + 1];
-          const int* row = bp + (int64_t)my_k * nb1;
-          pf0 = nx.b0 == tr.b1 ? pf1 : row[nx.b0];
-          pf1 = row[nx.b1];
+    // this thread's pieces of the tile, one per cached segment
+    int off_c[kRegSegs], len_c[kRegSegs];
+#pragma unroll
+    for (int g = 0; g < kRegSegs; ++g) {
+      off_c[g] = 0; len_c[g] = 0;
+      const int e = g * kSegCap + tid;
+      if (cached && e < d) {
+        if (use_table) {
+          off_c[g] = pf0[g];
+          len_c[g] = pf1[g] - pf0[g];
+          if (t + 1 < rr.count) {
+            const TileRec nx = ns->rec[t + 1];
+            const int* row = bp + (int64_t)ck[g] * nb1;
+            pf0[g] = nx.b0 == tr.b1 ? pf1[g] : row[nx.b0];
+            pf1[g] = row[nx.b1];
+          }
+        } else {   // one segment, no table
+          long long ps;
+          piece_range(ck[g], crs[g], my_re, tr.b0, tr.b1, t_lo, t_hi, sorted, bp, nb1, b_col, ps, len_c[g]);
+          off_c[g] = (int)(ps - crs[g]);
         }
-      } else {
-        piece_range(my_k, my_rs, my_re, tr.b0, tr.b1, t_lo, t_hi, sorted, bp, nb1, b_col, s, len);
       }
     }
+    // piece of segment sg for this thread
     auto seg_piece = [&](int sg, long long& ps, int& plen, T& pav) {
+      if (cached) {
+        static_assert(kRegSegs == 4, "the selects below cover four segments");
+        const int o = sg == 0 ? off_c[0] : sg == 1 ? off_c[1] : sg == 2 ? off_c[2] : off_c[3];
+        plen = sg == 0 ? len_c[0] : sg == 1 ? len_c[1] : sg == 2 ? len_c[2] : len_c[3];
+        ps = (sg == 0 ? crs[0] : sg == 1 ? crs[1] : sg == 2 ? crs[2] : crs[3]) + o;
+        pav = sg == 0 ? cav[0] : sg == 1 ? cav[1] : sg == 2 ? cav[2] : cav[3];
+        return;
+      }
       ps = 0; plen = 0; pav = T(0);
       const int e = sg * kSegCap + tid;
       if (e < d && e < (sg + 1) * kSegCap) {
@@ -583,6 +699,10 @@ __device__ __forceinline__ void num_dense_run(const RunRec rr, NumScratch<T>* ns
         piece_range(k, b_rp[k], b_rp[k + 1], tr.b0, tr.b1, t_lo, t_hi, sorted, bp, nb1, b_col, ps, plen);
       }
     };
+    long long s = 0;
+    int len = 0;
+    T my_av = T(0);
+    if (nseg == 1) seg_piece(0, s, len, my_av);
     __syncthreads();   // the previous tile's output has left the tile area
     if (direct) {
       double* acc = reinterpret_cast<double*>(tile);                      // kBlkCols sums, indexed by column
@@ -592,7 +712,8 @@ __device__ __forceinline__ void num_dense_run(const RunRec rr, NumScratch<T>* ns
         double2* a2 = reinterpret_cast<double2*>(acc);
         for (int r = tid; r < kBlkCols / 2; r += kDenseThreads) a2[r] = make_double2(0.0, 0.0);
       }
-      if (tid < kBlkCols / 32) flags[tid] = 0;
+      // which columns exist: the flag words are in the plan's list, or are rebuilt by the pass
+      if (tid < kBlkCols / 32) flags[tid] = have_list ? (unsigned)col_list[list_at + tr.out + tid] : 0u;
       for (int sg = 0; sg < nseg; ++sg) {
         T av = my_av;
         if (nseg > 1) seg_piece(sg, s, len, av);
@@ -601,7 +722,7 @@ __device__ __forceinline__ void num_dense_run(const RunRec rr, NumScratch<T>* ns
         chunk_pass<true, T>(np, nchunks, ns, b_col, b_val, [&](int c, T a, T b) {
           if (!CHECK || (c >= t_lo && (int64_t)c < t_hi)) {
             const int rel = c - t_lo;
-            atomicOr(&flags[rel >> 5], 1u << (rel & 31));
+            if (!have_list) atomicOr(&flags[rel >> 5], 1u << (rel & 31));
             __hip_atomic_fetch_add(&acc[rel], (double)a * (double)b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
           }
         });
@@ -637,9 +758,44 @@ __device__ __forceinline__ void num_dense_run(const RunRec rr, NumScratch<T>* ns
       uint2* fc = reinterpret_cast<uint2*>(tile);                         // per word: .x flag bits, .y rank of its first column
       double* acc = reinterpret_cast<double*>(tile + (size_t)nw * 8);     // count sums, by rank
       int* stage = reinterpret_cast<int*>(acc + count);                   // count columns, by rank
+      // with a column list: the first batch of its entries is on its way while the workspace is set up
+      const int32_t* lst = col_list + (have_list ? list_at + tr.out : 0);
+      int lc[kListBatch], lp[kListBatch];   // kListBatch loads in flight per thread
+      auto fetch_list = [&](int j0) {
+#pragma unroll
+        for (int i = 0; i < kListBatch; ++i) {
+          const int j = j0 + i * kDenseThreads + tid;
+          lc[i] = j < count ? lst[j] : -1;
+          lp[i] = ((tid & 63) == 0 && j > 0 && j < count) ? lst[j - 1] : -1;   // left neighbour of the wave's first entry
+        }
+      };
+      if (have_list) fetch_list(0);
       for (int w = tid; w < nw; w += kDenseThreads) fc[w] = make_uint2(0u, 0u);
-      // pass 1: which columns of the tile exist in the row
       int np = 0, nchunks = 0;
+      if (have_list) {
+        // the symbolic phase left the tile's columns (ascending) in the plan: flag bits and ranks
+        // come from that list, and the list is this tile's run of C's column indices
+        for (int r = tid; r < count; r += kDenseThreads) acc[r] = 0.0;
+        if (nseg == 1) tile_pieces(ns, s, len, my_av, np, nchunks); else __syncthreads();
+        for (int j0 = 0; j0 < count; j0 += kListBatch * kDenseThreads) {
+          if (j0 > 0) fetch_list(j0);
+#pragma unroll
+          for (int i = 0; i < kListBatch; ++i) {
+            const int j = j0 + i * kDenseThreads + tid;
+            const int c = lc[i];
+            int prev = __shfl_up(c, 1, kWave);
+            if ((tid & 63) == 0) prev = lp[i];
+            if (c >= 0) {
+              const int rel = c - t_lo;
+              atomicOr(&fc[rel >> 5].x, 1u << (rel & 31));
+              if (prev < 0 || ((prev - t_lo) >> 5) != (rel >> 5)) fc[rel >> 5].y = (unsigned)j;
+              c_col[out + j] = c;
+            }
+          }
+        }
+        __syncthreads();
+      } else {
+      // pass 1: which columns of the tile exist in the row
       for (int sg = 0; sg < nseg; ++sg) {
         T av = my_av;
         if (nseg > 1) seg_piece(sg, s, len, av);
@@ -686,6 +842,7 @@ __device__ __forceinline__ void num_dense_run(const RunRec rr, NumScratch<T>* ns
       }
       for (int r = tid; r < count; r += kDenseThreads) acc[r] = 0.0;
       __syncthreads();
+      }
       // pass 2: accumulate a_ik * b_kj at the rank of column j
       for (int sg = 0; sg < nseg; ++sg) {
         if (nseg > 1) {
@@ -693,21 +850,26 @@ __device__ __forceinline__ void num_dense_run(const RunRec rr, NumScratch<T>* ns
           seg_piece(sg, s, len, av);
           tile_pieces(ns, s, len, av, np, nchunks);
         }
-        chunk_pass<true, T>(np, nchunks, ns, b_col, b_val, [&](int c, T a, T b) {
+        auto add = [&](int c, T a, T b) {
           if (!CHECK || (c >= t_lo && (int64_t)c < t_hi)) {
             const int rel = c - t_lo;
             const uint2 w = fc[rel >> 5];
             const int rank = (int)w.y + __popc(w.x & ((1u << (rel & 31)) - 1u));
             __hip_atomic_fetch_add(&acc[rank], (double)a * (double)b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
           }
-        });
+        };
+        chunk_pass<true, T>(np, nchunks, ns, b_col, b_val, add);
         if (nseg > 1) __syncthreads();
       }
       __syncthreads();
       // compress: sums and columns are already in ascending column order
-      for (int r = tid; r < count; r += kDenseThreads) {
-        c_val[out + r] = (T)acc[r];
-        c_col[out + r] = stage[r];
+      if (have_list) {
+        for (int r = tid; r < count; r += kDenseThreads) c_val[out + r] = (T)acc[r];
+      } else {
+        for (int r = tid; r < count; r += kDenseThreads) {
+          c_val[out + r] = (T)acc[r];
+          c_col[out + r] = stage[r];
+        }
       }
     }
   }
@@ -720,6 +882,7 @@ __global__ __launch_bounds__(kDenseThreads) void k_num_dense(Control* ctl, const
                                                              const T* __restrict__ a_val, const int64_t* __restrict__ b_rp,
                                                              const int32_t* __restrict__ b_col, const T* __restrict__ b_val,
                                                              int64_t n_cols, const int* __restrict__ bp, int nb1,
+                                                             const int32_t* __restrict__ col_list,
                                                              const int64_t* __restrict__ c_rp,
                                                              int32_t* __restrict__ c_col, T* __restrict__ c_val) {
   extern __shared__ __align__(16) unsigned char smem[];
@@ -745,9 +908,9 @@ __global__ __launch_bounds__(kDenseThreads) void k_num_dense(Control* ctl, const
     if (cls < 5 || cls > 6) continue;   // the row's numeric class is not this kernel's
     __syncthreads();
     if (sorted)
-      num_dense_run<T, false>(rr, ns, tile, true, a_col, a_val, b_rp, b_col, b_val, n_cols, bp, nb1, out_row, c_col, c_val);
+      num_dense_run<T, false>(rr, ns, tile, true, a_col, a_val, b_rp, b_col, b_val, n_cols, bp, nb1, col_list, out_row, c_col, c_val);
     else
-      num_dense_run<T, true>(rr, ns, tile, false, a_col, a_val, b_rp, b_col, b_val, n_cols, bp, nb1, out_row, c_col, c_val);
+      num_dense_run<T, true>(rr, ns, tile, false, a_col, a_val, b_rp, b_col, b_val, n_cols, bp, nb1, col_list, out_row, c_col, c_val);
   }
 }
 

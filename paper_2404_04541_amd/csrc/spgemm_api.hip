@@ -31,6 +31,7 @@ struct spgemm_context {
   int timing = 0;
   int force = 0;
   int direct_min = kDirectMinDefault;
+  int col_list = 1;
   std::string err = "";
   bool device_ready = false;
   int num_cus = 0;
@@ -54,6 +55,9 @@ struct spgemm_plan_s {
   int blk_ptr_cols = 0;      // column blocks + 1
   TileRec* tiles = nullptr;
   RunRec* runs = nullptr;
+  void* scratch3 = nullptr;  // column list of the ranked tiles (optional: sized from what the device has free)
+  int32_t* col_list = nullptr;
+  unsigned long long col_list_cap = 0;
   Control* ctl = nullptr;
   int64_t scan_blocks = 0;
   bool symbolic_done = false;
@@ -251,11 +255,27 @@ int alloc_dense_lists(spgemm_context* h, spgemm_plan_s* p, const spgemm_csr* B, 
   p->tiles = reinterpret_cast<TileRec*>(base + o_tiles);
   p->runs = reinterpret_cast<RunRec*>(base + o_runs);
   p->blk_ptr = with_bp ? reinterpret_cast<int*>(base + o_bp) : nullptr;
+  // Column list: the dense symbolic kernel leaves the columns of its ranked tiles there, which saves
+  // the numeric kernel one pass over those tiles' products.  At most `entries` are needed; take no
+  // more than a third of what the device has free, and do without if the allocation fails.
+  size_t free_b = 0, total_b = 0;
+  if (h->col_list && hipMemGetInfo(&free_b, &total_b) == hipSuccess) {
+    double want = entries * 4.0;
+    if (want > (double)free_b / 3.0) want = (double)free_b / 3.0;
+    const size_t bytes = ((size_t)want) & ~(size_t)255;
+    if (bytes >= 4096) {
+      p->scratch3 = dev_alloc(h, bytes);
+      if (p->scratch3) {
+        p->col_list = static_cast<int32_t*>(p->scratch3);
+        p->col_list_cap = bytes / 4;
+      }
+    }
+  }
   return SPGEMM_OK;
 }
 
-__global__ void k_set_caps(Control* ctl, unsigned tile_cap, unsigned run_cap) {
-  if (threadIdx.x == 0) { ctl->tile_cap = tile_cap; ctl->run_cap = run_cap; }
+__global__ void k_set_caps(Control* ctl, unsigned tile_cap, unsigned run_cap, unsigned long long list_cap) {
+  if (threadIdx.x == 0) { ctl->tile_cap = tile_cap; ctl->run_cap = run_cap; ctl->list_cap = list_cap; }
 }
 
 template <typename T>
@@ -274,7 +294,7 @@ int run_symbolic(spgemm_context* h, spgemm_plan_s* p, const spgemm_csr* A, const
   int rc = alloc_dense_lists(h, p, B, host, &tile_cap, &run_cap);
   if (rc) return rc;
   if (rows_dense > 0) {
-    hipLaunchKernelGGL(k_set_caps, dim3(1), dim3(64), 0, s, p->ctl, tile_cap, run_cap);
+    hipLaunchKernelGGL(k_set_caps, dim3(1), dim3(64), 0, s, p->ctl, tile_cap, run_cap, p->col_list_cap);
     if (p->blk_ptr) {
       Timer t(h, SPGEMM_K_BLOCK_PTR);
       const int64_t items = B->rows * (int64_t)p->blk_ptr_cols;
@@ -309,7 +329,7 @@ int run_symbolic(spgemm_context* h, spgemm_plan_s* p, const spgemm_csr* A, const
     if (rows_dense > 0) {
       Timer t(h, SPGEMM_K_SYM_DENSE);
       hipLaunchKernelGGL(k_sym_dense, dim3(grid_for(rows_dense, 1, h->num_cus)), dim3(kDenseThreads), kSymDenseLds, s, p->perm_sym,
-                         p->ctl, A->rowptr, A->colidx, B->rowptr, B->colidx, B->cols, p->ip, p->cnt, p->tiles, p->runs, h->direct_min,
+                         p->ctl, A->rowptr, A->colidx, B->rowptr, B->colidx, B->cols, p->ip, p->cnt, p->tiles, p->runs, p->col_list, h->direct_min,
                          staged);
     }
     {
@@ -380,7 +400,7 @@ int run_numeric(spgemm_context* h, spgemm_plan_s* p, const spgemm_csr* A, const 
     Timer t(h, SPGEMM_K_NUM_DENSE);
     hipLaunchKernelGGL(k_num_dense<T>, dim3(grid_for(rows_dense, 1, h->num_cus)), dim3(kDenseThreads), num_dense_lds<T>(), s, p->ctl,
                        p->bin, p->tiles, p->runs, A->colidx, a_val, B->rowptr, B->colidx, b_val, B->cols, p->blk_ptr,
-                       p->blk_ptr_cols, c_rp, c_col, c_val);
+                       p->blk_ptr_cols, p->col_list, c_rp, c_col, c_val);
   }
   HIP_TRY(h, hipGetLastError());
   return SPGEMM_OK;
@@ -426,8 +446,13 @@ int spgemm_set_option(spgemm_handle h, int option, int64_t value) {
       h->force = (int)value;
       return SPGEMM_OK;
     case SPGEMM_OPT_DIRECT_MIN:
-      if (value < 1 || value > 0x3fffffff) return fail(h, SPGEMM_INVALID_ARG, "direct-tile threshold takes 1..2^30-1");
+      // a direct block keeps its 256 flag words in the list space of its entries
+      if (value < kBlkWords || value > 0x3fffffff) return fail(h, SPGEMM_INVALID_ARG, "direct-tile threshold takes 256..2^30-1");
       h->direct_min = (int)value;
+      return SPGEMM_OK;
+    case SPGEMM_OPT_COLUMN_LIST:
+      if (value != 0 && value != 1) return fail(h, SPGEMM_INVALID_ARG, "column-list option takes 0 or 1");
+      h->col_list = (int)value;
       return SPGEMM_OK;
     default:
       return fail(h, SPGEMM_INVALID_ARG, "unknown option");
@@ -440,6 +465,7 @@ int spgemm_plan_destroy(spgemm_plan p) {
   if (!p) return SPGEMM_INVALID_ARG;
   dev_free(p->h, p->scratch);
   dev_free(p->h, p->scratch2);
+  dev_free(p->h, p->scratch3);
   delete p;
   return SPGEMM_OK;
 }

@@ -5,12 +5,14 @@ import numpy as np
 RTOL = {np.dtype(np.float64): 1e-12, np.dtype(np.float32): 1e-5}
 
 
-def gpu_product(A, B, force=0, handle=None, via="phases"):
+def gpu_product(A, B, force=0, handle=None, via="phases", options=None):
     """C = A*B on the GPU through the binding. Returns (rowptr, colidx, values) numpy arrays and stats."""
     import torch
     from paper_2404_04541_amd import binding as sg
     h = handle or sg.Handle()
     h.set_option(sg.OPT_FORCE_WORKSPACE, force)
+    for opt, value in (options or {}).items():
+        h.set_option(opt, value)
     dA, dB = sg.to_device(A), sg.to_device(B)
     if via == "single":
         Cd = sg.spgemm(h, dA, dB)

@@ -11,8 +11,8 @@ pytestmark = pytest.mark.gpu
 AUTO, LIST, HASH, DENSE, STAGED = 0, 1, 2, 3, 4
 
 
-def run(A, B, force=AUTO, what="", via="phases"):
-    got = gpu_product(A, B, force, via=via)
+def run(A, B, force=AUTO, what="", via="phases", options=None):
+    got = gpu_product(A, B, force, via=via, options=options)
     ref = assert_matches_oracle(A, B, got, what=what)
     st = got[3]
     if st is not None:
@@ -62,6 +62,19 @@ def test_rectangular_and_ttm_small():
     run(a, b, what="config4 small")
     a, m = W.config5(dim=64, nnz=40000)
     run(a, m, what="config5 small")
+
+
+@pytest.mark.parametrize("column_list", [1, 0])
+@pytest.mark.parametrize("direct_min", [4096, 256, 1 << 20])
+def test_dense_tiles_direct_ranked_with_and_without_column_list(column_list, direct_min):
+    # power-law rows: dense heads (direct tiles) and sparse tails (ranked tiles) in the same rows;
+    # the ranked tiles take their structure from the plan's column list or rebuild it themselves
+    from paper_2404_04541_amd import binding as sg
+    a, b = W.config3(scale=14)
+    st = run(a, b, DENSE, what=f"rmat 14 dense list={column_list} direct_min={direct_min}",
+             options={sg.OPT_COLUMN_LIST: column_list, sg.OPT_DIRECT_MIN: direct_min})
+    assert st["dense_tiles"] > 0
+    assert (st["dense_direct_tiles"] > 0) == (direct_min < (1 << 20))
 
 
 def test_dense_workspace_many_windows_and_tiles():

@@ -103,6 +103,7 @@ typedef struct {
   int64_t dense_tiles;        /* column tiles planned for the dense numeric kernel */
   int64_t dense_direct_tiles; /* of those, tiles accumulated by column (one pass) */
   int64_t dense_runs;         /* work items (runs of tiles of one row) */
+  int64_t dense_search_tiles; /* of the tiles, whole short rows whose ranks come from bisecting the column list */
 } spgemm_stats;
 
 /* Options for spgemm_set_option. */

@@ -54,7 +54,7 @@ class StatsStruct(C.Structure):
                 ("num_bin_rows", C.c_int64 * NUM_BINS), ("sym_bin_ip", C.c_int64 * NUM_BINS),
                 ("num_bin_ip", C.c_int64 * NUM_BINS), ("num_bin_nnz", C.c_int64 * NUM_BINS), ("kernel_ms", C.c_double * NUM_KERNEL_CLASSES),
                 ("kernel_launches", C.c_int32 * NUM_KERNEL_CLASSES), ("dense_tiles", C.c_int64),
-                ("dense_direct_tiles", C.c_int64), ("dense_runs", C.c_int64)]
+                ("dense_direct_tiles", C.c_int64), ("dense_runs", C.c_int64), ("dense_search_tiles", C.c_int64)]
 
 
 _lib = None
@@ -131,7 +131,7 @@ class Plan:
                 "kernel_ms": dict(zip(KERNEL_CLASS_NAMES, st.kernel_ms)),
                 "kernel_launches": dict(zip(KERNEL_CLASS_NAMES, st.kernel_launches)),
                 "dense_tiles": int(st.dense_tiles), "dense_direct_tiles": int(st.dense_direct_tiles),
-                "dense_runs": int(st.dense_runs)}
+                "dense_runs": int(st.dense_runs), "dense_search_tiles": int(st.dense_search_tiles)}
 
     def destroy(self):
         if self.ptr:

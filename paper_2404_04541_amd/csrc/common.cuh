@@ -34,6 +34,7 @@ struct Control {
   unsigned tile_cursor, run_cursor;   // tile / run records written by the dense symbolic kernel
   unsigned tile_cap, run_cap;         // capacity of the two lists (set by the host)
   unsigned direct_tiles;              // how many of the tiles are direct
+  unsigned search_tiles;              // how many are searched tiles
   unsigned long long list_cursor, list_cap;   // entries used / available in the plan's column list
   int error;                      // nonzero: a device-side input check failed
   int b_sorted;                   // 1 when every B row is strictly ascending
@@ -52,6 +53,13 @@ __device__ __forceinline__ void wave_sync() {
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
   __builtin_amdgcn_wave_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// The same for LDS traffic only: global loads and stores of the wave stay in flight.
+__device__ __forceinline__ void wave_sync_lds() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
 }
 
 template <int GROUP>

@@ -37,11 +37,14 @@ constexpr int kRankEntryBytes = 12;               // sum + column per entry of a
 constexpr int kDirectMinDefault = 4096; // a block with at least this many entries becomes a direct tile
 constexpr int kRunTiles = 16;           // tiles handed to a workgroup at a time
 constexpr int kDirectBit = 1 << 30;     // in TileRec::cnt
+constexpr int kSearchBit = 1 << 29;     // in TileRec::cnt: a searched tile (ranks by bisection of the column list)
+constexpr int kCountMask = kSearchBit - 1;
+constexpr int kSearchCap = 11264;       // entries of a searched tile (column 4 B + sum 8 B each)
 constexpr int kSegCap = 1024;           // A entries described in LDS at a time (numeric)
 constexpr int kBlkWords = kBlkCols / 32;
 constexpr int kListStage = 320;          // entries that a wave gathers in LDS before writing them to the column list
 constexpr int kListBatch = 6;           // column-list loads in flight per thread
-constexpr int kRegSegs = 4;             // segments of A entries that the numeric kernel keeps in registers
+constexpr int kRegSegs = 2;             // segments of A entries that the numeric kernel keeps in registers
 constexpr long long kListBias = 1LL << 40;   // RunRec::list holds position + bias (so that -1 can mean "none")
 
 struct TileRec { int b0, b1, cnt, out; };     // blocks [b0, b1), entries (| kDirectBit), offset inside the row of C
@@ -223,7 +226,7 @@ struct TilePlan {
   int cum[kSpanBlocks + 1];
   int nxt[kSpanBlocks];
   TileRec rec[kSpanBlocks];
-  int ntiles, ndirect;
+  int ntiles, ndirect, nruns;
   unsigned tile_base, run_base;
   int row_out;
   int span_out0;          // row_out when the span began
@@ -259,9 +262,8 @@ __device__ __forceinline__ int prev_bit128(unsigned long long lo, unsigned long 
 // A block with at least direct_min entries is a direct tile of its own; the blocks between
 // are grouped greedily into ranked tiles of at most kTileBudget bytes
 // (kRankBlkBytes per block + kRankEntryBytes per entry).  Records land in tp->rec, their number in tp->ntiles.
-// First part (wave 0): entry prefix over the blocks, the span's total, and room in the plan's
-// column list for the span's entries (without room the numeric kernel rebuilds the flags itself).
-__device__ __forceinline__ void plan_head(TilePlan* tp, Control* ctl, int nb, bool count_only) {
+// First part (wave 0): entry prefix over the blocks and the span's total.
+__device__ __forceinline__ void plan_head(TilePlan* tp, int nb, bool count_only) {
   const int l = lane_id();
   const int c0 = l < nb ? tp->blk_cnt[l] : 0;
   const int c1 = l + 64 < nb ? tp->blk_cnt[l + 64] : 0;
@@ -275,16 +277,11 @@ __device__ __forceinline__ void plan_head(TilePlan* tp, Control* ctl, int nb, bo
     tp->cum[128] = total;
     tp->ntiles = 0;
     tp->ndirect = 0;
-    if (count_only) {   // the row's numeric class needs no tiles
-      tp->row_out += total;
-    } else if (total > 0 && ctl->list_cap > 0) {
-      const unsigned long long at = atomicAdd(&ctl->list_cursor, (unsigned long long)total);
-      if (at + (unsigned long long)total <= ctl->list_cap) tp->list_base = (long long)at;
-    }
+    if (count_only) tp->row_out += total;   // the row's numeric class needs no tiles
   }
 }
 
-// Second part (wave 0): the tile records.
+// Second part (wave 0): the tile records (direct and ranked tiles).
 __device__ __forceinline__ void plan_tail(TilePlan* tp, int nb, int block0, int direct_min) {
   const int l = lane_id();
   const int c0 = l < nb ? tp->blk_cnt[l] : 0;
@@ -359,9 +356,12 @@ __global__ __launch_bounds__(kDenseThreads) void k_sym_dense(const int* __restri
   const bool sorted = ctl->b_sorted != 0;
   const int64_t span = (int64_t)kSymFlagWords * 32;
   const int tid = threadIdx.x;
-  while (true) {
-    const int row = next_dense_row(perm, ctl, &rs->s_row);
-    if (row < 0) break;
+  const unsigned row_lo = ctl->offset[0][4], row_hi = ctl->offset[0][7];   // the dense bins, heaviest class last
+  const unsigned tile_cap = ctl->tile_cap, run_cap = ctl->run_cap;
+  const unsigned long long list_cap = ctl->list_cap;
+  int row = next_dense_row(perm, ctl, &rs->s_row);
+  int next_row = -1;   // (thread 0) the row after this one, fetched while this one is in the works
+  while (row >= 0) {
     const int64_t a0 = a_rp[row];
     const int d = (int)(a_rp[row + 1] - a0);
     if (tid == 0) tp->row_out = 0;
@@ -401,84 +401,136 @@ __global__ __launch_bounds__(kDenseThreads) void k_sym_dense(const int* __restri
       }
       __syncthreads();
       const bool count_only = ip[row] <= no_tiles_ip;
-      if (tid < kWave) plan_head(tp, ctl, nb, count_only);
+      const bool whole_row = n_cols <= span;
+      const bool last_span = c1 >= n_cols;
+      const int block0 = (int)(c0 >> kBlkShift);
+      if (tid < kWave) {
+        plan_head(tp, nb, count_only);
+        if (!count_only) plan_tail(tp, nb, block0, direct_min);
+      }
+      __syncthreads();
+      if (tid == 0) {
+        // Everything this span needs from the plan's shared lists, and the next row, in one round trip:
+        // room for the entries in the column list (without it the numeric kernel rebuilds the flags
+        // itself), tile and run records.  A span that is the whole row, got room in the list and has at
+        // most kSearchCap entries becomes one searched tile (the records planned above stay unused).
+        const int total = tp->cum[128];
+        const int nt = tp->ntiles;
+        const int nr = (nt + kRunTiles - 1) / kRunTiles;
+        const bool want_list = !count_only && total > 0 && list_cap > 0;
+        unsigned long long at = 0;
+        unsigned tb = 0, rb = 0, nx = 0;
+        if (want_list) at = atomicAdd(&ctl->list_cursor, (unsigned long long)total);
+        if (nt > 0) { tb = atomicAdd(&ctl->tile_cursor, (unsigned)nt); rb = atomicAdd(&ctl->run_cursor, (unsigned)nr); }
+        if (last_span) nx = atomicAdd(&ctl->work[0], 1u);
+        const bool listed = want_list && at + (unsigned long long)total <= list_cap;
+        tp->list_base = listed ? (long long)at : -1;
+        tp->tile_base = tb;
+        tp->run_base = rb;
+        tp->nruns = nr;
+        if (nt > 0 && (tb + (unsigned)nt > tile_cap || rb + (unsigned)nr > run_cap)) {
+          ctl->error = 3;   // cannot happen when the host sized the lists from the bound
+          tp->ntiles = 0;
+          tp->nruns = 0;
+        } else if (listed && whole_row && total <= kSearchCap && nt > 0) {
+          tp->rec[0] = TileRec{block0, block0 + nb, total | kSearchBit, tp->span_out0};
+          tp->ntiles = 1;
+          atomicAdd(&ctl->search_tiles, 1u);
+        } else if (tp->ndirect > 0) {
+          atomicAdd(&ctl->direct_tiles, (unsigned)tp->ndirect);
+        }
+        if (last_span) next_row = nx < row_hi - row_lo ? perm[row_hi - 1 - nx] : -1;
+      }
       __syncthreads();
       const long long lb = tp->list_base;
-      if (!count_only) {
-        // wave 0 cuts the tiles while the other waves already write the column list
-        if (tid < kWave) plan_tail(tp, nb, (int)(c0 >> kBlkShift), direct_min);
-        if (lb >= 0) {
-          // wave v owns flag words [2048 v, 2048 v + 2048), i.e. blocks 8 v .. 8 v + 7; the list position
-          // of a block's first entry is its entry prefix.  Sparse blocks: the columns are decoded, a round
-          // of 64 words with few entries is gathered in LDS first and leaves as one coalesced run.
-          // Direct blocks: the numeric kernel wants the flag words themselves (their 256 words fit
-          // in the space of the block's entries).
-          const int wave = tid >> 6, lane = tid & 63;
-          int* wst = reinterpret_cast<int*>(rs) + wave * kListStage;   // the piece walker's scratch is free now
-          for (int bl = 0; bl < kSpanBlocks / kDenseWaves; ++bl) {
-            const int blk = wave * (kSpanBlocks / kDenseWaves) + bl;
-            const int cb = tp->blk_cnt[blk];
-            if (cb == 0) continue;
-            int running = tp->cum[blk];
-            if (cb >= direct_min) {
+      const int nt = tp->ntiles;
+      if (nt > 0 || tp->nruns > 0) {
+        if (tid < nt) tiles[tp->tile_base + tid] = tp->rec[tid];
+        if (tid < tp->nruns) {   // (runs behind the tiles in use stay empty: count 0)
+          const int left = nt - tid * kRunTiles;
+          runs[tp->run_base + tid] = RunRec{row, tp->tile_base + (unsigned)(tid * kRunTiles), left < 0 ? 0 : (left < kRunTiles ? left : kRunTiles), d, a0,
+                                            lb < 0 ? -1LL : lb - tp->span_out0 + kListBias};
+        }
+      }
+      if (lb >= 0) {
+        // wave v owns flag words [2048 v, 2048 v + 2048), i.e. blocks 8 v .. 8 v + 7; the list position
+        // of a block's first entry is its entry prefix.  Sparse blocks: the columns are decoded, a round
+        // with few entries is gathered in LDS first and leaves as one coalesced run.
+        // Direct blocks: the numeric kernel wants the flag words themselves (their 256 words fit
+        // in the space of the block's entries).
+        const int wave = tid >> 6, lane = tid & 63;
+        const bool searched = nt == 1 && (tp->rec[0].cnt & kSearchBit) != 0;
+        int* wst = reinterpret_cast<int*>(rs) + wave * kListStage;   // the piece walker's scratch is free now
+        for (int bl = 0; bl < kSpanBlocks / kDenseWaves; ++bl) {
+          const int blk = wave * (kSpanBlocks / kDenseWaves) + bl;
+          const int cb = tp->blk_cnt[blk];
+          if (cb == 0) continue;
+          int running = tp->cum[blk];
+          if (cb >= direct_min && !searched) {
 #pragma unroll
-              for (int q = 0; q < kBlkWords; q += kWave) col_list[lb + running + q + lane] = (int)flags[blk * kBlkWords + q + lane];
-              continue;
-            }
-            for (int q = 0; q < kBlkWords; q += kWave) {
-              const int w = blk * kBlkWords + q + lane;
-              unsigned bits = flags[w];
-              const int c = __popc(bits);
-              const int incl = wave_incl_scan(c);
-              const int tot = __shfl(incl, kWave - 1, kWave);
-              if (tot == 0) continue;
-              int excl = incl - c;
-              const int cbase = lo + w * 32;
-              if (tot <= kListStage) {
+            for (int q = 0; q < kBlkWords; q += kWave) col_list[lb + running + q + lane] = (int)flags[blk * kBlkWords + q + lane];
+            continue;
+          }
+          if (cb <= kListStage) {
+            // a sparse block in one round: lane l decodes words 4 l .. 4 l + 3
+            const uint4 v = reinterpret_cast<const uint4*>(flags)[blk * (kBlkWords / 4) + lane];
+            const int c = __popc(v.x) + __popc(v.y) + __popc(v.z) + __popc(v.w);
+            int excl = wave_incl_scan(c) - c;
+            const int cbase = lo + (blk * kBlkWords + lane * 4) * 32;
+            if (c) {
+              unsigned wd[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+              for (int k = 0; k < 4; ++k) {
+                unsigned bits = wd[k];
                 while (bits) {
                   const int b = __ffs((int)bits) - 1;
                   bits &= bits - 1;
-                  wst[excl++] = cbase + b;
-                }
-                wave_sync();
-                for (int j = lane; j < tot; j += kWave) col_list[lb + running + j] = wst[j];
-                wave_sync();
-              } else {
-                while (bits) {
-                  const int b = __ffs((int)bits) - 1;
-                  bits &= bits - 1;
-                  col_list[lb + running + excl++] = cbase + b;
+                  wst[excl++] = cbase + k * 32 + b;
                 }
               }
-              running += tot;
             }
+            wave_sync_lds();
+            for (int j = lane; j < cb; j += kWave) col_list[lb + running + j] = wst[j];
+            wave_sync_lds();
+            continue;
+          }
+          for (int q = 0; q < kBlkWords; q += kWave) {
+            const int w = blk * kBlkWords + q + lane;
+            unsigned bits = flags[w];
+            const int c = __popc(bits);
+            const int incl = wave_incl_scan(c);
+            const int tot = __shfl(incl, kWave - 1, kWave);
+            if (tot == 0) continue;
+            int excl = incl - c;
+            const int cbase = lo + w * 32;
+            if (tot <= kListStage) {
+              while (bits) {
+                const int b = __ffs((int)bits) - 1;
+                bits &= bits - 1;
+                wst[excl++] = cbase + b;
+              }
+              wave_sync_lds();
+              for (int j = lane; j < tot; j += kWave) col_list[lb + running + j] = wst[j];
+              wave_sync_lds();   // (the stores themselves need not have left before the next round)
+            } else {
+              while (bits) {
+                const int b = __ffs((int)bits) - 1;
+                bits &= bits - 1;
+                col_list[lb + running + excl++] = cbase + b;
+              }
+            }
+            running += tot;
           }
         }
       }
       __syncthreads();
-      const int nt = tp->ntiles;
-      const int nr = (nt + kRunTiles - 1) / kRunTiles;
-      if (tid == 0 && nt > 0) {
-        tp->tile_base = atomicAdd(&ctl->tile_cursor, (unsigned)nt);
-        tp->run_base = atomicAdd(&ctl->run_cursor, (unsigned)nr);
-        if (tp->ndirect) atomicAdd(&ctl->direct_tiles, (unsigned)tp->ndirect);
-        if (tp->tile_base + (unsigned)nt > ctl->tile_cap || tp->run_base + (unsigned)nr > ctl->run_cap) {
-          ctl->error = 3;   // cannot happen when the host sized the lists from the bound
-          tp->ntiles = 0;
-        }
-      }
-      __syncthreads();
-      if (tp->ntiles > 0) {
-        if (tid < nt) tiles[tp->tile_base + tid] = tp->rec[tid];
-        if (tid < nr) {
-          const int left = nt - tid * kRunTiles;
-          runs[tp->run_base + tid] = RunRec{row, tp->tile_base + (unsigned)(tid * kRunTiles), left < kRunTiles ? left : kRunTiles, d, a0,
-                                            lb < 0 ? -1LL : lb - tp->span_out0 + kListBias};
-        }
-      }
-      __syncthreads();
     }
-    if (tid == 0) cnt[row] = tp->row_out;
+    if (tid == 0) {
+      cnt[row] = tp->row_out;
+      rs->s_row = next_row;
+    }
+    __syncthreads();
+    row = rs->s_row;
   }
 }
 
@@ -523,10 +575,11 @@ __device__ __forceinline__ double lane_get(double v, int lane) { return __longlo
 // describes a chunk is wave-uniform: the descriptors of the pieces that a batch of chunks can
 // touch are fetched from LDS by one lane each and handed out with readlane, so a batch costs
 // one LDS round trip before its loads are issued.  f(column, a, b) is called per element
-// (a, b only meaningful when WITH_VALUES).
-template <bool WITH_VALUES, typename T, class F>
-__device__ __forceinline__ void chunk_pass(int np, int nchunks, const NumScratch<T>* ns, const int32_t* __restrict__ b_col,
-                                           const T* __restrict__ b_val, F f) {
+// (a, b only meaningful when WITH_VALUES); g(columns, a's, b's) gets a whole batch of
+// kChunkUnroll elements per lane (column -1: no element).
+template <bool WITH_VALUES, typename T, class G>
+__device__ __forceinline__ void chunk_pass_batches(int np, int nchunks, const NumScratch<T>* ns, const int32_t* __restrict__ b_col,
+                                                   const T* __restrict__ b_val, G g) {
   const int wave = uni(threadIdx.x >> 6), lane = threadIdx.x & 63;
   np = uni(np);
   nchunks = uni(nchunks);
@@ -572,10 +625,20 @@ __device__ __forceinline__ void chunk_pass(int np, int nchunks, const NumScratch
       }
     }
     p += q;
-#pragma unroll
-    for (int u = 0; u < kChunkUnroll; ++u)
-      if (col[u] >= 0) f(col[u], au[u], bv[u]);
+    g(col, au, bv);
   }
+}
+
+// chunk_pass with a functor f(column, a, b) per element.
+template <bool WITH_VALUES, typename T, class F>
+__device__ __forceinline__ void chunk_pass(int np, int nchunks, const NumScratch<T>* ns, const int32_t* __restrict__ b_col,
+                                           const T* __restrict__ b_val, F f) {
+  chunk_pass_batches<WITH_VALUES, T>(np, nchunks, ns, b_col, b_val,
+                                     [&](const int (&col)[kChunkUnroll], const T (&au)[kChunkUnroll], const T (&bv)[kChunkUnroll]) {
+#pragma unroll
+                                       for (int u = 0; u < kChunkUnroll; ++u)
+                                         if (col[u] >= 0) f(col[u], au[u], bv[u]);
+                                     });
 }
 
 // The piece [s, s + len) of B row k that falls into the tile (blocks [b0, b1), columns [t_lo, t_hi)).
@@ -653,7 +716,8 @@ __device__ __forceinline__ void num_dense_run(const RunRec rr, NumScratch<T>* ns
   for (int t = 0; t < rr.count; ++t) {
     const TileRec tr = ns->rec[t];
     const bool direct = (tr.cnt & kDirectBit) != 0;
-    const int count = tr.cnt & (kDirectBit - 1);
+    const bool searched = (tr.cnt & kSearchBit) != 0;
+    const int count = tr.cnt & kCountMask;
     const int t_lo = tr.b0 << kBlkShift;
     int64_t t_hi = (int64_t)tr.b1 << kBlkShift;
     if (t_hi > n_cols) t_hi = n_cols;
@@ -684,11 +748,11 @@ __device__ __forceinline__ void num_dense_run(const RunRec rr, NumScratch<T>* ns
     // piece of segment sg for this thread
     auto seg_piece = [&](int sg, long long& ps, int& plen, T& pav) {
       if (cached) {
-        static_assert(kRegSegs == 4, "the selects below cover four segments");
-        const int o = sg == 0 ? off_c[0] : sg == 1 ? off_c[1] : sg == 2 ? off_c[2] : off_c[3];
-        plen = sg == 0 ? len_c[0] : sg == 1 ? len_c[1] : sg == 2 ? len_c[2] : len_c[3];
-        ps = (sg == 0 ? crs[0] : sg == 1 ? crs[1] : sg == 2 ? crs[2] : crs[3]) + o;
-        pav = sg == 0 ? cav[0] : sg == 1 ? cav[1] : sg == 2 ? cav[2] : cav[3];
+        static_assert(kRegSegs == 2, "the selects below cover two segments");
+        const int o = sg == 0 ? off_c[0] : off_c[1];
+        plen = sg == 0 ? len_c[0] : len_c[1];
+        ps = (sg == 0 ? crs[0] : crs[1]) + o;
+        pav = sg == 0 ? cav[0] : cav[1];
         return;
       }
       ps = 0; plen = 0; pav = T(0);
@@ -704,7 +768,61 @@ __device__ __forceinline__ void num_dense_run(const RunRec rr, NumScratch<T>* ns
     T my_av = T(0);
     if (nseg == 1) seg_piece(0, s, len, my_av);
     __syncthreads();   // the previous tile's output has left the tile area
-    if (direct) {
+    if (searched) {
+      // the tile's columns (from the plan's list) and their sums, by rank; a product finds the rank of
+      // its column by bisection, so the tile may be as wide as the matrix
+      int* cols = reinterpret_cast<int*>(tile);
+      double* acc = reinterpret_cast<double*>(tile + (((size_t)count * 4 + 7) & ~(size_t)7));
+      const int32_t* lst = col_list + list_at + tr.out;
+      for (int j0 = 0; j0 < count; j0 += kListBatch * kDenseThreads) {
+        int lc[kListBatch];
+#pragma unroll
+        for (int i = 0; i < kListBatch; ++i) {
+          const int j = j0 + i * kDenseThreads + tid;
+          lc[i] = j < count ? lst[j] : -1;
+        }
+#pragma unroll
+        for (int i = 0; i < kListBatch; ++i) {
+          const int j = j0 + i * kDenseThreads + tid;
+          if (j < count) {
+            cols[j] = lc[i];
+            acc[j] = 0.0;
+            c_col[out + j] = lc[i];
+          }
+        }
+      }
+      int top = 1;   // largest power of two below count
+      while (top * 2 < count) top *= 2;
+      for (int sg = 0; sg < nseg; ++sg) {
+        T av = my_av;
+        if (nseg > 1) seg_piece(sg, s, len, av);
+        int np, nchunks;
+        tile_pieces(ns, s, len, av, np, nchunks);   // (its barriers also publish cols and the cleared sums)
+        chunk_pass_batches<true, T>(np, nchunks, ns, b_col, b_val,
+                                    [&](const int (&c)[kChunkUnroll], const T (&a)[kChunkUnroll], const T (&b)[kChunkUnroll]) {
+          // last position whose column is <= c (the column is in the list); four bisections
+          // advance in lockstep so that their LDS reads overlap
+#pragma unroll
+          for (int u0 = 0; u0 < kChunkUnroll; u0 += 4) {
+            int lo[4] = {0, 0, 0, 0};
+            for (int step = top; step > 0; step >>= 1) {
+#pragma unroll
+              for (int u = 0; u < 4; ++u) {
+                const int mid = lo[u] + step;
+                if (mid < count && cols[mid < count ? mid : 0] <= c[u0 + u]) lo[u] = mid;
+              }
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+              if (c[u0 + u] >= 0)
+                __hip_atomic_fetch_add(&acc[lo[u]], (double)a[u0 + u] * (double)b[u0 + u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+          }
+        });
+        if (nseg > 1) __syncthreads();
+      }
+      __syncthreads();
+      for (int r = tid; r < count; r += kDenseThreads) c_val[out + r] = (T)acc[r];
+    } else if (direct) {
       double* acc = reinterpret_cast<double*>(tile);                      // kBlkCols sums, indexed by column
       int* stage = reinterpret_cast<int*>(tile + (size_t)kBlkCols * 8);   // kBlkCols columns, by rank
       unsigned* flags = reinterpret_cast<unsigned*>(tile + (size_t)kBlkCols * 12);   // kBlkCols / 32
@@ -892,11 +1010,13 @@ __global__ __launch_bounds__(kDenseThreads) void k_num_dense(Control* ctl, const
   const bool sorted = ctl->b_sorted != 0;
   const int tid = threadIdx.x;
   const unsigned nruns = ctl->run_cursor;
+  unsigned next_run = 0;   // (thread 0) drawn one run ahead, so that the counter's round trip is off the path
+  if (tid == 0) next_run = atomicAdd(&ctl->work[1], 1u);
   while (true) {
     __syncthreads();
     if (tid == 0) {
-      const unsigned r = atomicAdd(&ctl->work[1], 1u);
-      ns->s_run = r < nruns ? (int)r : -1;
+      ns->s_run = next_run < nruns ? (int)next_run : -1;
+      if (next_run < nruns) next_run = atomicAdd(&ctl->work[1], 1u);
     }
     __syncthreads();
     const int run = ns->s_run;
@@ -905,7 +1025,7 @@ __global__ __launch_bounds__(kDenseThreads) void k_num_dense(Control* ctl, const
     const int cls = numbin[rr.row];
     const int64_t out_row = c_rp[rr.row];
     if (tid < rr.count) ns->rec[tid] = tiles[rr.first + tid];
-    if (cls < 5 || cls > 6) continue;   // the row's numeric class is not this kernel's
+    if (cls < 5 || cls > 6 || rr.count == 0) continue;   // the row's numeric class is not this kernel's
     __syncthreads();
     if (sorted)
       num_dense_run<T, false>(rr, ns, tile, true, a_col, a_val, b_rp, b_col, b_val, n_cols, bp, nb1, col_list, out_row, c_col, c_val);

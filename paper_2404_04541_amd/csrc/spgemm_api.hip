@@ -289,7 +289,9 @@ int run_symbolic(spgemm_context* h, spgemm_plan_s* p, const spgemm_csr* A, const
   const unsigned* hist = host.hist[0];
   const int64_t rows_dense = (int64_t)hist[4] + hist[5] + hist[6];
   // rows of at most this many products never reach the dense numeric kernel (0: class unavailable)
-  const int staged = (h->force != 3 && ceil_div(B->cols, kStWinCols) <= kStMaxWindows) ? staged_cap<T>() : 0;
+  // (the staged class is taken only on request: short rows whose columns are in the plan's list
+  // become searched tiles of the dense kernel, which costs them one global round trip less)
+  const int staged = (h->force == 4 && ceil_div(B->cols, kStWinCols) <= kStMaxWindows) ? staged_cap<T>() : 0;
   unsigned tile_cap = 0, run_cap = 0;
   int rc = alloc_dense_lists(h, p, B, host, &tile_cap, &run_cap);
   if (rc) return rc;
@@ -559,6 +561,7 @@ int spgemm_symbolic(spgemm_handle h, const spgemm_csr* A, const spgemm_csr* B, i
   p->stats.dense_tiles = host.tile_cursor;
   p->stats.dense_direct_tiles = host.direct_tiles;
   p->stats.dense_runs = host.run_cursor;
+  p->stats.dense_search_tiles = host.search_tiles;
   p->symbolic_done = true;
   *nnz_c = host.nnz_c;
   *plan = p;

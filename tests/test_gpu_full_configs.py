@@ -106,7 +106,8 @@ def test_config3_rmat_scale20():
     a, b = W.config3()
     st, _, _ = check_full(a, b, budget=1.5e8)
     assert st["nnz_c"] > 2 ** 32      # the row pointer must be 64-bit
-    assert st["num_bin_rows"][4] > 0 and st["num_bin_rows"][5] > 0 and st["num_bin_rows"][6] > 0
+    assert st["num_bin_rows"][5] > 0 and st["num_bin_rows"][6] > 0
+    assert st["dense_search_tiles"] > 0 and st["dense_tiles"] > st["dense_search_tiles"]
 
 
 def test_config4_rectangular():

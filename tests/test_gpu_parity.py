@@ -53,8 +53,10 @@ def test_rmat_small_scale_power_law(force):
     a, b = W.config3(scale=13)
     st = run(a, b, force, what=f"rmat scale 13 force={force}")
     if force == AUTO:
-        assert st["num_bin_rows"][4] > 0, "mid rows must reach the staged coordinate list"
         assert sum(st["num_bin_rows"][5:7]) > 0, "long rows must reach the dense workspace"
+        assert st["dense_search_tiles"] > 0, "short dense rows become searched tiles"
+    if force == STAGED:
+        assert st["num_bin_rows"][4] > 0, "rows of few products must reach the staged coordinate list"
 
 
 def test_rectangular_and_ttm_small():
@@ -70,11 +72,16 @@ def test_dense_tiles_direct_ranked_with_and_without_column_list(column_list, dir
     # power-law rows: dense heads (direct tiles) and sparse tails (ranked tiles) in the same rows;
     # the ranked tiles take their structure from the plan's column list or rebuild it themselves
     from paper_2404_04541_amd import binding as sg
-    a, b = W.config3(scale=14)
-    st = run(a, b, DENSE, what=f"rmat 14 dense list={column_list} direct_min={direct_min}",
+    a, b = W.config3(scale=15)
+    st = run(a, b, DENSE, what=f"rmat 15 dense list={column_list} direct_min={direct_min}",
              options={sg.OPT_COLUMN_LIST: column_list, sg.OPT_DIRECT_MIN: direct_min})
-    assert st["dense_tiles"] > 0
-    assert (st["dense_direct_tiles"] > 0) == (direct_min < (1 << 20))
+    ranked = st["dense_tiles"] - st["dense_search_tiles"] - st["dense_direct_tiles"]
+    assert ranked > 0 or direct_min == 256, "hub rows need ranked tiles unless every block counts as dense"
+    assert (st["dense_search_tiles"] > 0) == (column_list == 1)   # searched tiles need the list
+    if direct_min == 256:
+        assert st["dense_direct_tiles"] > 0
+    if direct_min == 1 << 20:
+        assert st["dense_direct_tiles"] == 0
 
 
 def test_dense_workspace_many_windows_and_tiles():

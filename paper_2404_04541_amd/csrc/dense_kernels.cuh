@@ -47,6 +47,15 @@ constexpr int kListBatch = 6;           // column-list loads in flight per threa
 constexpr int kRegSegs = 2;             // segments of A entries that the numeric kernel keeps in registers
 constexpr long long kListBias = 1LL << 40;   // RunRec::list holds position + bias (so that -1 can mean "none")
 
+// Stores and loads of data that passes through the numeric kernel once (the result, the plan's
+// column list): the non-temporal hint keeps it from displacing B, which is re-read all the time,
+// from the caches.  (Not for the symbolic kernel's list writes: partial lines written with the
+// hint are not combined, which costs more than it saves.)
+template <typename V>
+__device__ __forceinline__ void stream_store(V* p, V v) { __builtin_nontemporal_store(v, p); }
+template <typename V>
+__device__ __forceinline__ V stream_load(const V* p) { return __builtin_nontemporal_load(p); }
+
 struct TileRec { int b0, b1, cnt, out; };     // blocks [b0, b1), entries (| kDirectBit), offset inside the row of C
 // tiles [first, first + count) of one row; its A entries [a0, a0 + d); list: where entry 0 of the
 // row sits in the column list, plus kListBias (-1: the row has no list)
@@ -546,6 +555,7 @@ struct NumScratch {
   int c_len[kSegCap];          // piece length
   T c_av[kSegCap];             // a_ik of the piece
   TileRec rec[kRunTiles];
+  RunRec rr;                   // the run in the works
   int red[2 * kDenseWaves];
   int s_run;
   int pad;
@@ -680,7 +690,8 @@ __device__ __forceinline__ void num_dense_run(const RunRec rr, NumScratch<T>* ns
                                               const int64_t* __restrict__ b_rp, const int32_t* __restrict__ b_col,
                                               const T* __restrict__ b_val, int64_t n_cols, const int* __restrict__ bp, int nb1,
                                               const int32_t* __restrict__ col_list,
-                                              int64_t out_row, int32_t* __restrict__ c_col, T* __restrict__ c_val) {
+                                              int64_t out_row, int32_t* __restrict__ c_col, T* __restrict__ c_val,
+                                              const int (&pre_k)[kRegSegs], const T (&pre_av)[kRegSegs]) {
   const int tid = threadIdx.x;
   const bool have_list = rr.list >= 0;
   const long long list_at = rr.list - kListBias;
@@ -701,8 +712,8 @@ __device__ __forceinline__ void num_dense_run(const RunRec rr, NumScratch<T>* ns
     ck[g] = 0; pf0[g] = 0; pf1[g] = 0; crs[g] = 0; cav[g] = T(0);
     const int e = g * kSegCap + tid;
     if (cached && e < d) {
-      ck[g] = a_col[a0 + e];
-      cav[g] = a_val[a0 + e];
+      ck[g] = pre_k[g];     // (fetched by the caller together with the run's tile records)
+      cav[g] = pre_av[g];
       crs[g] = b_rp[ck[g]];
       if (!use_table) my_re = b_rp[ck[g] + 1];
       if (use_table) {
@@ -779,7 +790,7 @@ __device__ __forceinline__ void num_dense_run(const RunRec rr, NumScratch<T>* ns
 #pragma unroll
         for (int i = 0; i < kListBatch; ++i) {
           const int j = j0 + i * kDenseThreads + tid;
-          lc[i] = j < count ? lst[j] : -1;
+          lc[i] = j < count ? stream_load(&lst[j]) : -1;
         }
 #pragma unroll
         for (int i = 0; i < kListBatch; ++i) {
@@ -787,7 +798,7 @@ __device__ __forceinline__ void num_dense_run(const RunRec rr, NumScratch<T>* ns
           if (j < count) {
             cols[j] = lc[i];
             acc[j] = 0.0;
-            c_col[out + j] = lc[i];
+            stream_store(&c_col[out + j], lc[i]);
           }
         }
       }
@@ -821,7 +832,7 @@ __device__ __forceinline__ void num_dense_run(const RunRec rr, NumScratch<T>* ns
         if (nseg > 1) __syncthreads();
       }
       __syncthreads();
-      for (int r = tid; r < count; r += kDenseThreads) c_val[out + r] = (T)acc[r];
+      for (int r = tid; r < count; r += kDenseThreads) stream_store(&c_val[out + r], (T)acc[r]);
     } else if (direct) {
       double* acc = reinterpret_cast<double*>(tile);                      // kBlkCols sums, indexed by column
       int* stage = reinterpret_cast<int*>(tile + (size_t)kBlkCols * 8);   // kBlkCols columns, by rank
@@ -868,8 +879,8 @@ __device__ __forceinline__ void num_dense_run(const RunRec rr, NumScratch<T>* ns
       }
       __syncthreads();
       for (int r = tid; r < count; r += kDenseThreads) {
-        c_val[out + r] = (T)acc[r];
-        c_col[out + r] = stage[r];
+        stream_store(&c_val[out + r], (T)acc[r]);
+        stream_store(&c_col[out + r], stage[r]);
       }
     } else {
       const int nw = (tr.b1 - tr.b0) * (kBlkCols / 32);                   // 32-bit flag words
@@ -883,7 +894,7 @@ __device__ __forceinline__ void num_dense_run(const RunRec rr, NumScratch<T>* ns
 #pragma unroll
         for (int i = 0; i < kListBatch; ++i) {
           const int j = j0 + i * kDenseThreads + tid;
-          lc[i] = j < count ? lst[j] : -1;
+          lc[i] = j < count ? stream_load(&lst[j]) : -1;
           lp[i] = ((tid & 63) == 0 && j > 0 && j < count) ? lst[j - 1] : -1;   // left neighbour of the wave's first entry
         }
       };
@@ -907,7 +918,7 @@ __device__ __forceinline__ void num_dense_run(const RunRec rr, NumScratch<T>* ns
               const int rel = c - t_lo;
               atomicOr(&fc[rel >> 5].x, 1u << (rel & 31));
               if (prev < 0 || ((prev - t_lo) >> 5) != (rel >> 5)) fc[rel >> 5].y = (unsigned)j;
-              c_col[out + j] = c;
+              stream_store(&c_col[out + j], c);
             }
           }
         }
@@ -982,11 +993,11 @@ __device__ __forceinline__ void num_dense_run(const RunRec rr, NumScratch<T>* ns
       __syncthreads();
       // compress: sums and columns are already in ascending column order
       if (have_list) {
-        for (int r = tid; r < count; r += kDenseThreads) c_val[out + r] = (T)acc[r];
+        for (int r = tid; r < count; r += kDenseThreads) stream_store(&c_val[out + r], (T)acc[r]);
       } else {
         for (int r = tid; r < count; r += kDenseThreads) {
-          c_val[out + r] = (T)acc[r];
-          c_col[out + r] = stage[r];
+          stream_store(&c_val[out + r], (T)acc[r]);
+          stream_store(&c_col[out + r], stage[r]);
         }
       }
     }
@@ -1010,27 +1021,53 @@ __global__ __launch_bounds__(kDenseThreads) void k_num_dense(Control* ctl, const
   const bool sorted = ctl->b_sorted != 0;
   const int tid = threadIdx.x;
   const unsigned nruns = ctl->run_cursor;
-  unsigned next_run = 0;   // (thread 0) drawn one run ahead, so that the counter's round trip is off the path
-  if (tid == 0) next_run = atomicAdd(&ctl->work[1], 1u);
+  // Thread 0 draws runs ahead of their use: the counter value for the run after next and the record
+  // of the next run are on their way while the current run is in the works.
+  unsigned drawn = 0;
+  RunRec coming{};
+  bool have_coming = false;
+  if (tid == 0) {
+    const unsigned first = atomicAdd(&ctl->work[1], 1u);
+    drawn = atomicAdd(&ctl->work[1], 1u);
+    have_coming = first < nruns;
+    if (have_coming) coming = runs[first];
+  }
   while (true) {
     __syncthreads();
     if (tid == 0) {
-      ns->s_run = next_run < nruns ? (int)next_run : -1;
-      if (next_run < nruns) next_run = atomicAdd(&ctl->work[1], 1u);
+      ns->s_run = have_coming ? 1 : -1;
+      if (have_coming) ns->rr = coming;
+      have_coming = drawn < nruns;
+      if (have_coming) {
+        coming = runs[drawn];
+        drawn = atomicAdd(&ctl->work[1], 1u);
+      }
     }
     __syncthreads();
-    const int run = ns->s_run;
-    if (run < 0) break;
-    const RunRec rr = runs[run];
+    if (ns->s_run < 0) break;
+    const RunRec rr = ns->rr;
+    if (rr.count == 0) continue;   // a record that its row did not need
+    // one round trip: the row's class and position in C, the run's tile records, its A entries
     const int cls = numbin[rr.row];
     const int64_t out_row = c_rp[rr.row];
     if (tid < rr.count) ns->rec[tid] = tiles[rr.first + tid];
-    if (cls < 5 || cls > 6 || rr.count == 0) continue;   // the row's numeric class is not this kernel's
+    int pre_k[kRegSegs];
+    T pre_av[kRegSegs];
+#pragma unroll
+    for (int g = 0; g < kRegSegs; ++g) {
+      pre_k[g] = 0; pre_av[g] = T(0);
+      const int e = g * kSegCap + tid;
+      if (e < rr.d && rr.d <= kRegSegs * kSegCap) {
+        pre_k[g] = a_col[rr.a0 + e];
+        pre_av[g] = a_val[rr.a0 + e];
+      }
+    }
+    if (cls < 5 || cls > 6) continue;   // the row's numeric class is not this kernel's
     __syncthreads();
     if (sorted)
-      num_dense_run<T, false>(rr, ns, tile, true, a_col, a_val, b_rp, b_col, b_val, n_cols, bp, nb1, col_list, out_row, c_col, c_val);
+      num_dense_run<T, false>(rr, ns, tile, true, a_col, a_val, b_rp, b_col, b_val, n_cols, bp, nb1, col_list, out_row, c_col, c_val, pre_k, pre_av);
     else
-      num_dense_run<T, true>(rr, ns, tile, false, a_col, a_val, b_rp, b_col, b_val, n_cols, bp, nb1, col_list, out_row, c_col, c_val);
+      num_dense_run<T, true>(rr, ns, tile, false, a_col, a_val, b_rp, b_col, b_val, n_cols, bp, nb1, col_list, out_row, c_col, c_val, pre_k, pre_av);
   }
 }
 

@@ -31,9 +31,9 @@ constexpr int kSymFlagWords = 32768;    // 2^20 columns per symbolic span (128 K
 constexpr int kBlkCols = 8192;          // tile boundaries are multiples of this many columns
 constexpr int kBlkShift = 13;
 constexpr int kSpanBlocks = kSymFlagWords * 32 / kBlkCols;   // 128 blocks per symbolic span
-constexpr int kTileBudget = 135 * 1024; // LDS bytes of one numeric tile (flags + ranks + sums + columns)
+constexpr int kTileBudget = 135 * 1024; // LDS bytes of one numeric tile (flags + ranks + sums)
 constexpr int kRankBlkBytes = kBlkCols / 32 * 8;   // flag word + rank per 32 columns of a ranked tile
-constexpr int kRankEntryBytes = 12;               // sum + column per entry of a ranked tile
+constexpr int kRankEntryBytes = 8;                // sum per entry of a ranked tile (its column goes straight to C)
 constexpr int kDirectMinDefault = 4096; // a block with at least this many entries becomes a direct tile
 constexpr int kRunTiles = 16;           // tiles handed to a workgroup at a time
 constexpr int kDirectBit = 1 << 30;     // in TileRec::cnt
@@ -886,7 +886,6 @@ __device__ __forceinline__ void num_dense_run(const RunRec rr, NumScratch<T>* ns
       const int nw = (tr.b1 - tr.b0) * (kBlkCols / 32);                   // 32-bit flag words
       uint2* fc = reinterpret_cast<uint2*>(tile);                         // per word: .x flag bits, .y rank of its first column
       double* acc = reinterpret_cast<double*>(tile + (size_t)nw * 8);     // count sums, by rank
-      int* stage = reinterpret_cast<int*>(acc + count);                   // count columns, by rank
       // with a column list: the first batch of its entries is on its way while the workspace is set up
       const int32_t* lst = col_list + (have_list ? list_at + tr.out : 0);
       int lc[kListBatch], lp[kListBatch];   // kListBatch loads in flight per thread
@@ -966,7 +965,7 @@ __device__ __forceinline__ void num_dense_run(const RunRec rr, NumScratch<T>* ns
         while (bits) {   // columns are decoded from the flag words ("boolean indexing")
           const int b = __ffs((int)bits) - 1;
           bits &= bits - 1;
-          stage[excl++] = cbase + b;
+          c_col[out + excl++] = cbase + b;   // (short runs per lane: this route is the fallback without a column list)
         }
       }
       for (int r = tid; r < count; r += kDenseThreads) acc[r] = 0.0;
@@ -995,10 +994,7 @@ __device__ __forceinline__ void num_dense_run(const RunRec rr, NumScratch<T>* ns
       if (have_list) {
         for (int r = tid; r < count; r += kDenseThreads) stream_store(&c_val[out + r], (T)acc[r]);
       } else {
-        for (int r = tid; r < count; r += kDenseThreads) {
-          stream_store(&c_val[out + r], (T)acc[r]);
-          stream_store(&c_col[out + r], stage[r]);
-        }
+        for (int r = tid; r < count; r += kDenseThreads) stream_store(&c_val[out + r], (T)acc[r]);
       }
     }
   }

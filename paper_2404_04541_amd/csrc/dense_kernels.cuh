@@ -561,7 +561,7 @@ struct NumScratch {
   int pad;
 };
 
-constexpr int kChunkUnroll = 12;
+constexpr int kChunkUnroll = 8;
 
 __device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
 __device__ __forceinline__ long long uni64(long long v) {

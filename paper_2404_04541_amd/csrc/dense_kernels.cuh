@@ -43,7 +43,7 @@ constexpr int kSearchCap = 11264;       // entries of a searched tile (column 4 
 constexpr int kSegCap = 1024;           // A entries described in LDS at a time (numeric)
 constexpr int kBlkWords = kBlkCols / 32;
 constexpr int kListStage = 320;          // entries that a wave gathers in LDS before writing them to the column list
-constexpr int kListBatch = 6;           // column-list loads in flight per thread
+constexpr int kListBatch = 4;           // column-list loads in flight per thread
 constexpr int kRegSegs = 2;             // segments of A entries that the numeric kernel keeps in registers
 constexpr long long kListBias = 1LL << 40;   // RunRec::list holds position + bias (so that -1 can mean "none")
 

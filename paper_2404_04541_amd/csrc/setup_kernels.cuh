@@ -75,18 +75,38 @@ __global__ __launch_bounds__(256) void k_count_rows(int64_t m, int64_t nnz_a, in
   }
   const long long lo = rp[0], hi = rp[nr];
   bool badcol = false;
-  for (long long p = lo + tid; p < hi; p += 256) {
-    const int k = a_col[p];
-    if (k < 0 || k >= b_rows) { badcol = true; continue; }
-    const long long len = b_rp[k + 1] - b_rp[k];
-    if (len < 0) { badcol = true; continue; }
-    // row of entry p: last t with rp[t] <= p
-    int a = 0, b = nr;
-    while (b - a > 1) {
-      const int mid = (a + b) >> 1;
-      if (rp[mid] <= p) a = mid; else b = mid;
+  // four entries per thread and round, so that their (dependent) loads overlap
+  for (long long p0 = lo + tid; p0 < hi; p0 += 256 * 4) {
+    int k[4];
+    long long len[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const long long p = p0 + u * 256;
+      k[u] = p < hi ? a_col[p] : -1;
     }
-    if (len) atomicAdd(&ipl[a], (unsigned long long)len);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const long long p = p0 + u * 256;
+      len[u] = 0;
+      if (p < hi) {
+        if (k[u] < 0 || k[u] >= b_rows) { badcol = true; continue; }
+        len[u] = b_rp[k[u] + 1] - b_rp[k[u]];
+        if (len[u] < 0) { badcol = true; len[u] = 0; }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const long long p = p0 + u * 256;
+      if (len[u] > 0) {
+        // row of entry p: last t with rp[t] <= p
+        int a = 0, b = nr;
+        while (b - a > 1) {
+          const int mid = (a + b) >> 1;
+          if (rp[mid] <= p) a = mid; else b = mid;
+        }
+        atomicAdd(&ipl[a], (unsigned long long)len[u]);
+      }
+    }
   }
   if (badcol) ctl->error = 1;
   __syncthreads();

@@ -178,26 +178,35 @@ __global__ void k_bin_offsets(Control* ctl, int phase) {
   }
 }
 
-// Scatter row ids into their bins.  Each wave ballots per bin, its first lane of that bin
-// reserves a run with one atomic, and lanes take their rank inside the ballot mask
-// (a wavefront-level prefix count), so a bin costs one atomic per wave.
-__global__ void k_bin_scatter(int64_t m, const unsigned char* __restrict__ bin, int* __restrict__ perm,
-                              Control* ctl, int phase) {
+// Scatter row ids into their bins.  Each wave ballots per bin and ranks its lanes inside the
+// ballot mask (a wavefront-level prefix count); the waves of a workgroup add their counts up in
+// LDS, so that a bin costs one global atomic per workgroup of 1024 rows.
+constexpr int kScatterThreads = 1024;
+__global__ __launch_bounds__(kScatterThreads) void k_bin_scatter(int64_t m, const unsigned char* __restrict__ bin, int* __restrict__ perm,
+                                                                 Control* ctl, int phase) {
+  constexpr int kWaves = kScatterThreads / kWave;
+  __shared__ unsigned wcount[kNumBins][kWaves];   // per bin: rows of each wave, then their prefix
+  __shared__ unsigned base[kNumBins];
   if (ctl->error) return;
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  const bool valid = i < m;
-  const int b = valid ? bin[i] : -1;
-  const int lane = lane_id();
+  const int b = i < m ? bin[i] : -1;
+  const int lane = lane_id(), wave = threadIdx.x >> 6;
   const unsigned long long below = lane == 0 ? 0ULL : (~0ULL >> (64 - lane));
+  int rank = 0;
   for (int v = 0; v < kNumBins - 1; ++v) {   // bin 7 holds rows with no work: not listed
     const unsigned long long mask = __ballot(b == v);
-    if (mask == 0) continue;
-    const int leader = __ffsll((long long)mask) - 1;
-    unsigned base = 0;
-    if (lane == leader) base = atomicAdd(&ctl->cursor[phase][v], (unsigned)__popcll(mask));
-    base = __shfl(base, leader, kWave);
-    if (b == v) perm[ctl->offset[phase][v] + base + __popcll(mask & below)] = (int)i;
+    if (lane == 0) wcount[v][wave] = (unsigned)__popcll(mask);
+    if (b == v) rank = __popcll(mask & below);
   }
+  __syncthreads();
+  if (threadIdx.x < kNumBins - 1) {
+    const int v = threadIdx.x;
+    unsigned run = 0;
+    for (int w = 0; w < kWaves; ++w) { const unsigned c = wcount[v][w]; wcount[v][w] = run; run += c; }
+    base[v] = run ? atomicAdd(&ctl->cursor[phase][v], run) : 0u;
+  }
+  __syncthreads();
+  if (b >= 0 && b < kNumBins - 1) perm[ctl->offset[phase][b] + base[b] + wcount[b][wave] + rank] = (int)i;
 }
 
 // ---- exclusive scan of int32 row counts into the int64 row pointer -------------------

@@ -212,7 +212,7 @@ int run_setup(spgemm_context* h, spgemm_plan_s* p, const spgemm_csr* A, const sp
     Timer t(h, SPGEMM_K_BIN);
     hipLaunchKernelGGL(k_bin_offsets, dim3(1), dim3(64), 0, s, p->ctl, 0);
     if (m > 0)
-      hipLaunchKernelGGL(k_bin_scatter, dim3((unsigned)ceil_div(m, 256)), dim3(256), 0, s, m, p->bin, p->perm_sym, p->ctl, 0);
+      hipLaunchKernelGGL(k_bin_scatter, dim3((unsigned)ceil_div(m, kScatterThreads)), dim3(kScatterThreads), 0, s, m, p->bin, p->perm_sym, p->ctl, 0);
   }
   HIP_TRY(h, hipGetLastError());
   HIP_TRY(h, hipMemcpyAsync(host, p->ctl, sizeof(Control), hipMemcpyDeviceToHost, s));
@@ -339,7 +339,7 @@ int run_symbolic(spgemm_context* h, spgemm_plan_s* p, const spgemm_csr* A, const
       hipLaunchKernelGGL(k_classify_numeric, dim3(grid_for(m, 256, (int64_t)h->num_cus * 8)), dim3(256), 0, s, m, p->ip, p->cnt,
                          p->bin, p->ctl, h->force, staged);
       hipLaunchKernelGGL(k_bin_offsets, dim3(1), dim3(64), 0, s, p->ctl, 1);
-      hipLaunchKernelGGL(k_bin_scatter, dim3((unsigned)ceil_div(m, 256)), dim3(256), 0, s, m, p->bin, p->perm_num, p->ctl, 1);
+      hipLaunchKernelGGL(k_bin_scatter, dim3((unsigned)ceil_div(m, kScatterThreads)), dim3(kScatterThreads), 0, s, m, p->bin, p->perm_num, p->ctl, 1);
     }
   }
   {

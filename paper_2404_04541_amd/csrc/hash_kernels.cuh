@@ -97,7 +97,7 @@ __global__ __launch_bounds__(256) void k_hash(const int* __restrict__ perm, cons
       // empty slots hold kEmptyKey = -1: turn them into the pad key so they sort last
       for (int t = gl; t < H; t += GROUP) if (keys[t] == kEmptyKey) keys[t] = kPadKey;
       group_sync<GROUP>();
-      bitonic_sort_lds<GROUP, double>(keys, vals, H, gl);
+      bitonic_sort_lds<GROUP, H, double>(keys, vals, gl);
       if (live) {
         const int64_t out = c_rp[row];
         const int n = (int)(c_rp[row + 1] - out);

@@ -123,7 +123,8 @@ enum {
   SPGEMM_OPT_DIRECT_MIN = 3,
   /* 1 (default): the plan keeps the column indices of the dense workspace's ranked tiles
    * (up to a third of the free device memory), which saves the numeric phase one pass over
-   * those tiles' products; rows that do not fit fall back to the two-pass route.  0: never. */
+   * those tiles' products; rows that do not fit fall back to the two-pass route.  0: never.
+   * A value of 4096 or more limits the list to that many bytes. */
   SPGEMM_OPT_COLUMN_LIST = 4
 };
 

@@ -31,7 +31,7 @@ struct spgemm_context {
   int timing = 0;
   int force = 0;
   int direct_min = kDirectMinDefault;
-  int col_list = 1;
+  int64_t col_list = 1;   // 0 off, 1 automatic size, larger: byte limit
   std::string err = "";
   bool device_ready = false;
   int num_cus = 0;
@@ -262,6 +262,7 @@ int alloc_dense_lists(spgemm_context* h, spgemm_plan_s* p, const spgemm_csr* B, 
   if (h->col_list && hipMemGetInfo(&free_b, &total_b) == hipSuccess) {
     double want = entries * 4.0;
     if (want > (double)free_b / 3.0) want = (double)free_b / 3.0;
+    if (h->col_list > 1 && want > (double)h->col_list) want = (double)h->col_list;
     const size_t bytes = ((size_t)want) & ~(size_t)255;
     if (bytes >= 4096) {
       p->scratch3 = dev_alloc(h, bytes);
@@ -453,8 +454,8 @@ int spgemm_set_option(spgemm_handle h, int option, int64_t value) {
       h->direct_min = (int)value;
       return SPGEMM_OK;
     case SPGEMM_OPT_COLUMN_LIST:
-      if (value != 0 && value != 1) return fail(h, SPGEMM_INVALID_ARG, "column-list option takes 0 or 1");
-      h->col_list = (int)value;
+      if (value < 0 || (value > 1 && value < 4096)) return fail(h, SPGEMM_INVALID_ARG, "column-list option takes 0, 1 or a byte limit of 4096 or more");
+      h->col_list = value;
       return SPGEMM_OK;
     default:
       return fail(h, SPGEMM_INVALID_ARG, "unknown option");

@@ -84,6 +84,25 @@ def test_dense_tiles_direct_ranked_with_and_without_column_list(column_list, dir
         assert st["dense_direct_tiles"] == 0
 
 
+def test_column_list_too_small_for_all_rows():
+    # a list of 256 KB holds the columns of some rows only: the others take the routes that need no list
+    from paper_2404_04541_amd import binding as sg
+    a, b = W.config3(scale=14)
+    for force in (AUTO, DENSE):
+        st = run(a, b, force, what=f"small list force={force}", options={sg.OPT_COLUMN_LIST: 1 << 18})
+        assert st["dense_tiles"] > st["dense_search_tiles"] > 0
+
+
+def test_wide_matrix_several_flag_list_spans_and_long_a_rows():
+    # more than 2^20 columns (the symbolic flag list covers the row in several spans) and rows of A
+    # with more entries than the numeric kernel keeps in registers
+    A = W.random_csr(24, 6000, 1500, 61)
+    B = W.random_csr(6000, 2_500_000, 40, 62)
+    for force in (AUTO, DENSE):
+        st = run(A, B, force, what=f"wide force={force}")
+        assert st["dense_tiles"] > 0
+
+
 def test_dense_workspace_many_windows_and_tiles():
     # wide column space (several windows) and rows with more entries than one tile holds
     A = W.random_csr(40, 3000, 900, 11)

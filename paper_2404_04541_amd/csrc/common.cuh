@@ -64,7 +64,7 @@ __device__ __forceinline__ void wave_sync_lds() {
 
 template <int GROUP>
 __device__ __forceinline__ void group_sync() {
-  if constexpr (GROUP <= kWave) wave_sync(); else __syncthreads();
+  if constexpr (GROUP <= kWave) wave_sync_lds(); else __syncthreads();
 }
 
 // Inclusive scan over the wave (all 64 lanes must call), on the DPP data path: four

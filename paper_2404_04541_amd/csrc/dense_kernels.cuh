@@ -2,21 +2,25 @@
 // paper's section 4.4, and the dense first-order workspace of section 7.2), one workgroup
 // of 1024 threads per row.
 //
-// Symbolic: a flag list with one bit per column (2^20 columns per span in 128 KB of LDS);
-//   products set bits, the row's size is the population count.  From the finished flag list
-//   the kernel also plans the row's numeric work: the column space is cut at multiples of
-//   kBlkCols columns into tiles, each small enough for the numeric workspace, and the tile
-//   list is stored in the plan.
-// Numeric : one tile at a time.
+// Symbolic (k_sym_dense): a flag list with one bit per column (2^20 columns per span in
+//   128 KB of LDS); products set bits, the row's size is the population count.  From the
+//   finished flag list the kernel also plans the row's numeric work: the column space is cut
+//   at multiples of kBlkCols columns into tiles, each small enough for the numeric workspace,
+//   and the row's column structure goes to the plan (decoded columns, or the flag words of
+//   direct blocks), so that the numeric phase need not find it again.
+// Numeric (k_num_dense), one tile at a time, one pass over the tile's products:
 //   direct tile (one block of kBlkCols columns in which the row is dense): sums live in a
-//     dense array indexed by column, flags record which columns exist; one pass over the
-//     products, then flags and sums are compressed ("boolean indexing" in the paper's words).
-//   ranked tile (a run of blocks in which the row is sparse): pass 1 rebuilds the flag bits,
-//     an exclusive prefix over the flag words gives every present column its rank, pass 2
-//     adds a_ik * b_kj at the rank of column j - LDS holds only columns that exist in C and
-//     the finished tile is already in ascending column order.
+//     dense array indexed by column; the flags say which exist; flags and sums are compressed
+//     at the end ("boolean indexing" in the paper's words).
+//   ranked tile (a run of blocks in which the row is sparse): an exclusive prefix over the flag
+//     words gives every present column its rank; a product adds a_ik * b_kj at the rank of
+//     column j - LDS holds only columns that exist in C and the finished tile is already in
+//     ascending column order.  Flags and ranks come from the plan's column list; without one,
+//     a first pass over the products rebuilds them.
+//   searched tile (a whole short row): the row's columns sit in LDS and a product finds its
+//     rank by bisection, so the tile's width does not matter.
 //   The piece of B row k that falls into a tile is found with two loads from a table of
-//   per-row block offsets (ascending B rows), so both passes touch only their own products.
+//   per-row block offsets (ascending B rows), so a pass touches only its own products.
 #pragma once
 #include "common.cuh"
 
@@ -167,18 +171,6 @@ __device__ __forceinline__ void stream_columns(int64_t a0, int d, const int32_t*
     }
     __syncthreads();
   }
-}
-
-// Sum over the workgroup; every thread gets the result.  red: kDenseWaves ints of LDS.
-__device__ __forceinline__ int block_sum(int v, int* red) {
-  v = wave_sum(v);
-  __syncthreads();
-  if (lane_id() == 0) red[threadIdx.x >> 6] = v;
-  __syncthreads();
-  int s = 0;
-#pragma unroll
-  for (int w = 0; w < kDenseWaves; ++w) s += red[w];
-  return s;
 }
 
 // For ascending B rows: bp[k * nb1 + b] = number of entries of row k with a column below

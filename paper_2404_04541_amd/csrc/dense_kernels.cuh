@@ -228,6 +228,7 @@ struct TilePlan {
   int nxt[kSpanBlocks];
   TileRec rec[kSpanBlocks];
   int ntiles, ndirect, nruns;
+  int next_block;         // list decode: the next block to hand to a wave
   unsigned tile_base, run_base;
   int row_out;
   int span_out0;          // row_out when the span began
@@ -428,6 +429,7 @@ __global__ __launch_bounds__(kDenseThreads) void k_sym_dense(const int* __restri
         tp->list_base = listed ? (long long)at : -1;
         tp->tile_base = tb;
         tp->run_base = rb;
+        tp->next_block = 0;
         tp->nruns = nr;
         if (nt > 0 && (tb + (unsigned)nt > tile_cap || rb + (unsigned)nr > run_cap)) {
           ctl->error = 3;   // cannot happen when the host sized the lists from the bound
@@ -454,16 +456,20 @@ __global__ __launch_bounds__(kDenseThreads) void k_sym_dense(const int* __restri
         }
       }
       if (lb >= 0) {
-        // wave v owns flag words [2048 v, 2048 v + 2048), i.e. blocks 8 v .. 8 v + 7; the list position
-        // of a block's first entry is its entry prefix.  Sparse blocks: the columns are decoded, a round
+        // The list position of a block's first entry is its entry prefix.  Sparse blocks: the columns are decoded, a round
         // with few entries is gathered in LDS first and leaves as one coalesced run.
         // Direct blocks: the numeric kernel wants the flag words themselves (their 256 words fit
         // in the space of the block's entries).
         const int wave = tid >> 6, lane = tid & 63;
         const bool searched = nt == 1 && (tp->rec[0].cnt & kSearchBit) != 0;
         int* wst = reinterpret_cast<int*>(rs) + wave * kListStage;   // the piece walker's scratch is free now
-        for (int bl = 0; bl < kSpanBlocks / kDenseWaves; ++bl) {
-          const int blk = wave * (kSpanBlocks / kDenseWaves) + bl;
+        // (blocks are handed out one at a time: their entry counts differ by orders of magnitude,
+        // so a fixed share per wave would leave most waves waiting for the one with the dense blocks)
+        while (true) {
+          int blk = 0;
+          if (lane == 0) blk = atomicAdd(&tp->next_block, 1);
+          blk = __builtin_amdgcn_readfirstlane(blk);
+          if (blk >= nb) break;
           const int cb = tp->blk_cnt[blk];
           if (cb == 0) continue;
           int running = tp->cum[blk];

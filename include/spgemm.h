@@ -125,7 +125,11 @@ enum {
    * (up to a third of the free device memory), which saves the numeric phase one pass over
    * those tiles' products; rows that do not fit fall back to the two-pass route.  0: never.
    * A value of 4096 or more limits the list to that many bytes. */
-  SPGEMM_OPT_COLUMN_LIST = 4
+  SPGEMM_OPT_COLUMN_LIST = 4,
+  /* 1 (default): for an ascending B the plan holds a table of per-row offsets at every 8192nd
+   * column (when it fits 1 GiB), which turns the search for a tile's piece of a B row into two
+   * loads.  0: never build it; pieces are found by bisection. */
+  SPGEMM_OPT_BLOCK_TABLE = 5
 };
 
 /* Create a handle bound to a HIP stream (hipStream_t passed as void*, null = default

@@ -32,6 +32,7 @@ struct spgemm_context {
   int force = 0;
   int direct_min = kDirectMinDefault;
   int64_t col_list = 1;   // 0 off, 1 automatic size, larger: byte limit
+  int block_table = 1;    // 0: never build the block-offset table of B (pieces are bisected)
   std::string err = "";
   bool device_ready = false;
   int num_cus = 0;
@@ -244,7 +245,7 @@ int alloc_dense_lists(spgemm_context* h, spgemm_plan_s* p, const spgemm_csr* B, 
   *run_cap = (unsigned)runs;
   p->blk_ptr_cols = (int)blocks + 1;
   const size_t bp_bytes = (size_t)B->rows * (size_t)p->blk_ptr_cols * 4;
-  const bool with_bp = host.b_sorted && B->nnz > 0 && bp_bytes <= ((size_t)1 << 30);
+  const bool with_bp = h->block_table && host.b_sorted && B->nnz > 0 && bp_bytes <= ((size_t)1 << 30);
   size_t off = 0;
   const size_t o_tiles = off; off = align_up(off + (size_t)*tile_cap * sizeof(TileRec));
   const size_t o_runs = off; off = align_up(off + (size_t)*run_cap * sizeof(RunRec));
@@ -452,6 +453,10 @@ int spgemm_set_option(spgemm_handle h, int option, int64_t value) {
       // a direct block keeps its 256 flag words in the list space of its entries
       if (value < kBlkWords || value > 0x3fffffff) return fail(h, SPGEMM_INVALID_ARG, "direct-tile threshold takes 256..2^30-1");
       h->direct_min = (int)value;
+      return SPGEMM_OK;
+    case SPGEMM_OPT_BLOCK_TABLE:
+      if (value != 0 && value != 1) return fail(h, SPGEMM_INVALID_ARG, "block-table option takes 0 or 1");
+      h->block_table = (int)value;
       return SPGEMM_OK;
     case SPGEMM_OPT_COLUMN_LIST:
       if (value < 0 || (value > 1 && value < 4096)) return fail(h, SPGEMM_INVALID_ARG, "column-list option takes 0, 1 or a byte limit of 4096 or more");

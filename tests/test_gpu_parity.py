@@ -93,6 +93,16 @@ def test_column_list_too_small_for_all_rows():
         assert st["dense_tiles"] > st["dense_search_tiles"] > 0
 
 
+@pytest.mark.parametrize("column_list", [1, 0])
+def test_without_block_table_pieces_are_bisected(column_list):
+    from paper_2404_04541_amd import binding as sg
+    a, b = W.config3(scale=14)
+    run(a, b, DENSE, what="no block table", options={sg.OPT_BLOCK_TABLE: 0, sg.OPT_COLUMN_LIST: column_list})
+    A = W.random_csr(24, 6000, 1500, 61)
+    B = W.random_csr(6000, 2_500_000, 40, 62)
+    run(A, B, DENSE, what="no block table, wide", options={sg.OPT_BLOCK_TABLE: 0, sg.OPT_COLUMN_LIST: column_list})
+
+
 def test_wide_matrix_several_flag_list_spans_and_long_a_rows():
     # more than 2^20 columns (the symbolic flag list covers the row in several spans) and rows of A
     # with more entries than the numeric kernel keeps in registers

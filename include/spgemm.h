@@ -182,6 +182,29 @@ int spgemm_get_stats(spgemm_plan plan, spgemm_stats* out);
 /* Text of the last error on this handle (never null; valid until the next call). */
 const char* spgemm_last_error(spgemm_handle h);
 
+/* ---- sparse tensor times sparse matrix over the tensor's third mode ------------------------
+ * Y(i,j,l) = sum_k X(i,j,k) M(k,l), computed on the row-wise path through the mode-3 unfolding
+ * of X (the index folding that section 7.4 of the paper describes for its comparison system):
+ * row i*J + j, column k.  X is given as device coordinate arrays xi, xj, xk (int32) and xval
+ * (nnz each, any order, borrowed); a coordinate that occurs several times contributes several
+ * products.  I*J and K must be below 2^31 - 1, nnz below 2^32 - 1.
+ * Output matrices are device CSR whose buffers come from the handle's allocator (release with
+ * its free or spgemm_free_device).  All three calls synchronise the handle's stream except
+ * sptensor_fold_mode3, which only enqueues.
+ * SPGEMM_INVALID_INPUT: a coordinate outside [0,I) x [0,J) x [0,K). */
+
+/* The unfolding itself: out = (I*J) x K CSR, columns ascending inside each row. */
+int sptensor_unfold_mode3(spgemm_handle h, int64_t I, int64_t J, int64_t K, int64_t nnz, const int32_t* xi,
+                          const int32_t* xj, const int32_t* xk, const void* xval, int32_t dtype, spgemm_csr* out);
+
+/* Y = X x_3 M as the unfolded (I*J) x M.cols CSR matrix: row i*J + j holds Y(i,j,:). */
+int spttm_mode3(spgemm_handle h, int64_t I, int64_t J, int64_t K, int64_t nnz, const int32_t* xi, const int32_t* xj,
+                const int32_t* xk, const void* xval, int32_t dtype, const spgemm_csr* M, spgemm_csr* Y);
+
+/* Coordinates of the entries of an unfolded result: yi[p], yj[p] (device, Y->nnz each, caller-owned)
+ * for entry p of Y; its third coordinate is Y->colidx[p]. */
+int sptensor_fold_mode3(spgemm_handle h, int64_t J, const spgemm_csr* Y, int32_t* yi, int32_t* yj);
+
 /* Library version: major*10000 + minor*100 + patch. */
 int spgemm_version(void);
 

@@ -108,3 +108,25 @@ def spgemm_rows(a_rowptr, a_col, a_val, b_rowptr, b_col, b_val, rows=None, row_l
 def spgemm(A, B, threads: int = 0) -> OracleResult:
     """Whole product for operands with .rowptr/.colidx/.values attributes."""
     return spgemm_rows(A.rowptr, A.colidx, A.values, B.rowptr, B.colidx, B.values, threads=threads)
+
+
+def unfold_mode3(shape, xi, xj, xk, xval):
+    """Mode-3 unfolding of a coordinate tensor X(i,j,k) (the index folding of the paper's section 7.4):
+    row i*J + j, column k, entries ordered by (row, column), repeated coordinates kept as separate
+    entries in their order of appearance.  Returns (rowptr int64, colidx int32, values)."""
+    I, J, K = (int(v) for v in shape)
+    xi = np.asarray(xi, dtype=np.int64); xj = np.asarray(xj, dtype=np.int64); xk = np.asarray(xk, dtype=np.int64)
+    if xi.size and (xi.min() < 0 or xi.max() >= I or xj.min() < 0 or xj.max() >= J or xk.min() < 0 or xk.max() >= K):
+        raise ValueError("coordinate out of range")
+    row = xi * J + xj
+    order = np.lexsort((np.arange(row.size), xk, row))   # by row, then column, then input position
+    rowptr = np.zeros(I * J + 1, dtype=np.int64)
+    np.cumsum(np.bincount(row, minlength=I * J), out=rowptr[1:])
+    return rowptr, xk[order].astype(np.int32), np.asarray(xval)[order]
+
+
+def spttm_mode3(shape, xi, xj, xk, xval, M, threads: int = 0) -> OracleResult:
+    """Y(i,j,l) = sum_k X(i,j,k) M(k,l) as the row-wise product of the mode-3 unfolding with M;
+    row i*J + j of the result holds Y(i,j,:)."""
+    rowptr, colidx, values = unfold_mode3(shape, xi, xj, xk, xval)
+    return spgemm_rows(rowptr, colidx, values, M.rowptr, M.colidx, M.values, threads=threads)

@@ -27,7 +27,8 @@ STATUS_NAMES = {0: "OK", -1: "INVALID_ARG", -2: "DIM_MISMATCH", -3: "DTYPE_MISMA
                 -5: "ALLOC_FAILED", -6: "HIP_ERROR", -7: "BAD_STATE", -8: "INVALID_INPUT"}
 
 EXPORTED = ("spgemm_create", "spgemm_destroy", "spgemm_set_option", "spgemm_symbolic", "spgemm_numeric", "spgemm",
-            "spgemm_free_device", "spgemm_plan_destroy", "spgemm_get_stats", "spgemm_last_error", "spgemm_version")
+            "spgemm_free_device", "spgemm_plan_destroy", "spgemm_get_stats", "spgemm_last_error", "spgemm_version",
+            "sptensor_unfold_mode3", "spttm_mode3", "sptensor_fold_mode3")
 
 
 class SpgemmError(RuntimeError):
@@ -79,6 +80,10 @@ def load_library():
     lib.spgemm_free_device.argtypes = [C.c_void_p, C.c_void_p]
     lib.spgemm_plan_destroy.argtypes = [C.c_void_p]
     lib.spgemm_get_stats.argtypes = [C.c_void_p, P(StatsStruct)]
+    tensor_args = [C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32]
+    lib.sptensor_unfold_mode3.argtypes = tensor_args + [P(CsrStruct)]
+    lib.spttm_mode3.argtypes = tensor_args + [P(CsrStruct), P(CsrStruct)]
+    lib.sptensor_fold_mode3.argtypes = [C.c_void_p, C.c_int64, P(CsrStruct), C.c_void_p, C.c_void_p]
     lib.spgemm_last_error.argtypes = [C.c_void_p]
     lib.spgemm_last_error.restype = C.c_char_p
     for name in EXPORTED:
@@ -249,3 +254,50 @@ def spgemm(handle: Handle, A: DeviceCSR, B: DeviceCSR) -> DeviceCSR:
         colidx = torch.empty(0, dtype=torch.int32, device=rowptr.device)
         values = torch.empty(0, dtype=vdt, device=rowptr.device)
     return DeviceCSR(int(sc.rows), int(sc.cols), rowptr, colidx, values)
+
+
+def _adopt_csr(handle: Handle, sc: CsrStruct, vdt: torch.dtype, device) -> DeviceCSR:
+    vsz = 4 if vdt == torch.float32 else 8
+    rowptr = handle.adopt(sc.rowptr, (sc.rows + 1) * 8, torch.int64)
+    if sc.nnz:
+        colidx = handle.adopt(sc.colidx, sc.nnz * 4, torch.int32)
+        values = handle.adopt(sc.values, sc.nnz * vsz, vdt)
+    else:
+        colidx = torch.empty(0, dtype=torch.int32, device=device)
+        values = torch.empty(0, dtype=vdt, device=device)
+    return DeviceCSR(int(sc.rows), int(sc.cols), rowptr, colidx, values)
+
+
+def _tensor_args(handle, shape, xi, xj, xk, xval):
+    I, J, K = (int(v) for v in shape)
+    n = int(xval.numel())
+    for t in (xi, xj, xk):
+        assert t.dtype == torch.int32 and t.is_contiguous() and t.numel() == n
+    assert xval.is_contiguous()
+    dt = {torch.float32: SPGEMM_F32, torch.float64: SPGEMM_F64}[xval.dtype]
+    ptr = lambda t: t.data_ptr() if n else None
+    return [handle.ptr, I, J, K, n, ptr(xi), ptr(xj), ptr(xk), ptr(xval), dt]
+
+
+def sptensor_unfold_mode3(handle: Handle, shape, xi, xj, xk, xval) -> DeviceCSR:
+    """Mode-3 unfolding of a coordinate tensor (device int32 coordinates, values): (I*J) x K CSR."""
+    sc = CsrStruct()
+    handle._check(handle.lib.sptensor_unfold_mode3(*_tensor_args(handle, shape, xi, xj, xk, xval), C.byref(sc)))
+    return _adopt_csr(handle, sc, xval.dtype, xval.device)
+
+
+def spttm_mode3(handle: Handle, shape, xi, xj, xk, xval, M: DeviceCSR) -> DeviceCSR:
+    """Y = X x_3 M as the unfolded (I*J) x M.cols CSR (row i*J + j holds Y(i,j,:))."""
+    sm, sc = M.struct(), CsrStruct()
+    handle._check(handle.lib.spttm_mode3(*_tensor_args(handle, shape, xi, xj, xk, xval), C.byref(sm), C.byref(sc)))
+    return _adopt_csr(handle, sc, xval.dtype, xval.device)
+
+
+def sptensor_fold_mode3(handle: Handle, J: int, Y: DeviceCSR):
+    """-> (yi, yj) int32 device tensors: first two coordinates of every entry of the unfolded Y."""
+    yi = torch.empty(Y.nnz, dtype=torch.int32, device=Y.rowptr.device)
+    yj = torch.empty(Y.nnz, dtype=torch.int32, device=Y.rowptr.device)
+    sy = Y.struct()
+    handle._check(handle.lib.sptensor_fold_mode3(handle.ptr, int(J), C.byref(sy), yi.data_ptr() if Y.nnz else None,
+                                                 yj.data_ptr() if Y.nnz else None))
+    return yi, yj

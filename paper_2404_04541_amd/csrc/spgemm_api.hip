@@ -16,6 +16,7 @@
 #include "hash_kernels.cuh"
 #include "dense_kernels.cuh"
 #include "staged_kernels.cuh"
+#include "tensor_kernels.cuh"
 
 using namespace spg;
 
@@ -637,6 +638,114 @@ int spgemm(spgemm_handle h, const spgemm_csr* A, const spgemm_csr* B, spgemm_csr
   }
   C->rows = A->rows; C->cols = B->cols; C->nnz = nnz; C->dtype = A->dtype;
   C->rowptr = rp; C->colidx = col; C->values = val;
+  return SPGEMM_OK;
+}
+
+
+int sptensor_unfold_mode3(spgemm_handle h, int64_t I, int64_t J, int64_t K, int64_t nnz, const int32_t* xi, const int32_t* xj,
+                          const int32_t* xk, const void* xval, int32_t dtype, spgemm_csr* out) {
+  if (!h) return SPGEMM_INVALID_ARG;
+  if (!out) return fail(h, SPGEMM_INVALID_ARG, "out is null");
+  if (I < 0 || J < 0 || K < 0 || nnz < 0) return fail(h, SPGEMM_INVALID_ARG, "negative size");
+  if (dtype != SPGEMM_F32 && dtype != SPGEMM_F64) return fail(h, SPGEMM_INVALID_ARG, "unknown dtype");
+  if (nnz > 0 && (!xi || !xj || !xk || !xval)) return fail(h, SPGEMM_INVALID_ARG, "coordinate or value array null with nnz > 0");
+  if (K >= 0x7fffffffLL || (J > 0 && I > 0x7ffffffeLL / J) || nnz >= 0xffffffffLL)
+    return fail(h, SPGEMM_UNSUPPORTED, "I*J and K must be below 2^31 - 1, nnz below 2^32 - 1");
+  std::memset(out, 0, sizeof(*out));
+  int rc = ensure_device(h);
+  if (rc) return rc;
+  hipStream_t s = h->stream;
+  const int64_t rows = I * J;
+  const size_t vsz = dtype == SPGEMM_F32 ? 4 : 8;
+  int64_t* rp = static_cast<int64_t*>(dev_alloc(h, (size_t)(rows + 1) * 8));
+  int32_t* col = nnz ? static_cast<int32_t*>(dev_alloc(h, (size_t)nnz * 4)) : nullptr;
+  void* val = nnz ? dev_alloc(h, (size_t)nnz * vsz) : nullptr;
+  const int64_t ntiles = ceil_div(nnz > 0 ? nnz : 1, kSortTile);
+  size_t off = 0;
+  const size_t o_k0 = off; off = align_up(off + (size_t)nnz * 8);
+  const size_t o_k1 = off; off = align_up(off + (size_t)nnz * 8);
+  const size_t o_i0 = off; off = align_up(off + (size_t)nnz * 4);
+  const size_t o_i1 = off; off = align_up(off + (size_t)nnz * 4);
+  const size_t o_h = off; off = align_up(off + (size_t)ntiles * 256 * 4);
+  const size_t o_bad = off; off = align_up(off + 4);
+  unsigned char* tmp = static_cast<unsigned char*>(dev_alloc(h, off));
+  auto release = [&](bool all) {
+    dev_free(h, tmp);
+    if (all) { dev_free(h, rp); dev_free(h, col); dev_free(h, val); }
+  };
+  if (!rp || !tmp || (nnz && (!col || !val))) { release(true); return fail(h, SPGEMM_ALLOC_FAILED, "allocation for the unfolding failed"); }
+  unsigned long long* keys[2] = {reinterpret_cast<unsigned long long*>(tmp + o_k0), reinterpret_cast<unsigned long long*>(tmp + o_k1)};
+  unsigned* idx[2] = {reinterpret_cast<unsigned*>(tmp + o_i0), reinterpret_cast<unsigned*>(tmp + o_i1)};
+  unsigned* hist = reinterpret_cast<unsigned*>(tmp + o_h);
+  int* bad = reinterpret_cast<int*>(tmp + o_bad);
+  int host_bad = 0;
+  hipError_t e = hipMemsetAsync(bad, 0, 4, s);
+  int cur = 0;
+  if (e == hipSuccess && nnz > 0) {
+    const unsigned g = grid_for(nnz, 256 * 4, (int64_t)h->num_cus * 32);
+    hipLaunchKernelGGL(k_tensor_keys, dim3(g), dim3(256), 0, s, nnz, I, J, K, xi, xj, xk, keys[0], idx[0], bad);
+    auto bits_of = [](int64_t n) { int b = 0; while (n > 1 && (1LL << b) < n) ++b; return b; };   // bits that hold 0 .. n-1
+    const int bits_k = bits_of(K), bits_r = bits_of(rows);
+    const unsigned gt = (unsigned)ceil_div(ntiles, kSortWgWaves);
+    for (int part = 0; part < 2; ++part) {
+      const int base = part == 0 ? 0 : 32, nbits = part == 0 ? bits_k : bits_r;
+      for (int shift = base; shift < base + nbits; shift += 8) {
+        hipLaunchKernelGGL(k_radix_hist, dim3(gt), dim3(256), 0, s, nnz, ntiles, shift, keys[cur], hist);
+        hipLaunchKernelGGL(k_scan_u32, dim3(1), dim3(1024), 0, s, ntiles * 256, hist);
+        hipLaunchKernelGGL(k_radix_scatter, dim3(gt), dim3(256), 0, s, nnz, ntiles, shift, keys[cur], idx[cur], hist, keys[1 - cur],
+                           idx[1 - cur]);
+        cur = 1 - cur;
+      }
+    }
+    if (dtype == SPGEMM_F32)
+      hipLaunchKernelGGL(k_tensor_compress<float>, dim3(g), dim3(256), 0, s, nnz, keys[cur], idx[cur], static_cast<const float*>(xval), col,
+                         static_cast<float*>(val));
+    else
+      hipLaunchKernelGGL(k_tensor_compress<double>, dim3(g), dim3(256), 0, s, nnz, keys[cur], idx[cur], static_cast<const double*>(xval), col,
+                         static_cast<double*>(val));
+  }
+  if (e == hipSuccess) {
+    hipLaunchKernelGGL(k_tensor_rowptr, dim3(grid_for(rows + 1, 256, (int64_t)h->num_cus * 32)), dim3(256), 0, s, nnz, rows, keys[cur], rp);
+    e = hipGetLastError();
+  }
+  if (e == hipSuccess) e = hipMemcpyAsync(&host_bad, bad, 4, hipMemcpyDeviceToHost, s);
+  if (e == hipSuccess) e = hipStreamSynchronize(s);
+  if (e != hipSuccess) { release(true); return fail(h, SPGEMM_HIP_ERROR, std::string("unfolding: ") + hipGetErrorString(e)); }
+  if (host_bad) { release(true); return fail(h, SPGEMM_INVALID_INPUT, "a tensor coordinate is outside its mode's range"); }
+  release(false);
+  out->rows = rows; out->cols = K; out->nnz = nnz; out->dtype = dtype;
+  out->rowptr = rp; out->colidx = col; out->values = val;
+  return SPGEMM_OK;
+}
+
+int spttm_mode3(spgemm_handle h, int64_t I, int64_t J, int64_t K, int64_t nnz, const int32_t* xi, const int32_t* xj, const int32_t* xk,
+                const void* xval, int32_t dtype, const spgemm_csr* M, spgemm_csr* Y) {
+  if (!h) return SPGEMM_INVALID_ARG;
+  if (!Y) return fail(h, SPGEMM_INVALID_ARG, "Y is null");
+  int rc = check_csr(h, M, "M");
+  if (rc) return rc;
+  if (M->rows != K) return fail(h, SPGEMM_DIM_MISMATCH, "M.rows differs from the tensor's third mode");
+  if (M->dtype != dtype) return fail(h, SPGEMM_DTYPE_MISMATCH, "tensor and matrix value types differ");
+  spgemm_csr X{};
+  rc = sptensor_unfold_mode3(h, I, J, K, nnz, xi, xj, xk, xval, dtype, &X);
+  if (rc) return rc;
+  rc = spgemm(h, &X, M, Y);
+  dev_free(h, const_cast<int64_t*>(X.rowptr));
+  dev_free(h, const_cast<int32_t*>(X.colidx));
+  dev_free(h, const_cast<void*>(X.values));
+  return rc;
+}
+
+int sptensor_fold_mode3(spgemm_handle h, int64_t J, const spgemm_csr* Y, int32_t* yi, int32_t* yj) {
+  if (!h) return SPGEMM_INVALID_ARG;
+  int rc = check_csr(h, Y, "Y");
+  if (rc) return rc;
+  if (J <= 0 || Y->rows % J != 0) return fail(h, SPGEMM_INVALID_ARG, "Y.rows is not a multiple of J");
+  if (Y->nnz > 0 && (!yi || !yj)) return fail(h, SPGEMM_INVALID_ARG, "coordinate arrays null with nnz > 0");
+  if (Y->nnz == 0 || Y->rows == 0) return SPGEMM_OK;
+  if ((rc = ensure_device(h))) return rc;
+  hipLaunchKernelGGL(k_tensor_fold, dim3(grid_for(Y->rows, 4, (int64_t)h->num_cus * 32)), dim3(256), 0, h->stream, Y->rows, J, Y->rowptr, yi, yj);
+  HIP_TRY(h, hipGetLastError());
   return SPGEMM_OK;
 }
 

@@ -13,7 +13,7 @@ HEADER = os.path.join(ROOT, "include", "spgemm.h")
 def declared_functions():
     text = open(HEADER).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(spgemm[a-z_]*)\s*\(", text)))
+    return sorted(set(re.findall(r"\b((?:spgemm|sptensor|spttm)[a-z_0-9]*)\s*\(", text)))
 
 
 @pytest.fixture(scope="module")

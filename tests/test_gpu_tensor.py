@@ -1,0 +1,90 @@
+"""GPU parity of the sparse tensor-times-matrix entry points (mode-3 unfolding on the GPU, the
+row-wise product, folding back) against the CPU checker."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2404_04541_amd import workloads as W
+from helpers import RTOL
+
+pytestmark = pytest.mark.gpu
+
+
+def to_dev(x):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(x)).cuda()
+
+
+def coords(shape, nnz, seed, distinct):
+    I, J, K = shape
+    idx = np.arange(nnz, dtype=np.uint64)
+    xi = W.rand_below(seed, 1, idx, I).astype(np.int32)
+    xj = W.rand_below(seed, 2, idx, J).astype(np.int32)
+    xk = W.rand_below(seed, 3, idx, K).astype(np.int32)
+    if distinct:
+        lin = (xi.astype(np.int64) * J + xj) * K + xk
+        _, first = np.unique(lin, return_index=True)
+        first.sort()
+        xi, xj, xk = xi[first], xj[first], xk[first]
+    return xi, xj, xk
+
+
+@pytest.mark.parametrize("shape,nnz,distinct,dtype", [((7, 5, 11), 150, True, np.float64), ((40, 33, 300), 50000, False, np.float64),
+                                                      ((300, 200, 70000), 400000, True, np.float32), ((3, 3, 3), 0, True, np.float64)])
+def test_unfold_ttm_fold(shape, nnz, distinct, dtype):
+    import torch
+    from paper_2404_04541_amd import binding as sg
+    I, J, K = shape
+    xi, xj, xk = coords(shape, nnz, 7, distinct)
+    vals = W.draw_values(xi.size, -1.0, 1.0, dtype, 7, 4)
+    M = W.random_csr(K, 500, 6, 9, dtype=dtype)
+    h = sg.Handle()
+    dxi, dxj, dxk, dv = to_dev(xi), to_dev(xj), to_dev(xk), to_dev(vals)
+    U = sg.sptensor_unfold_mode3(h, shape, dxi, dxj, dxk, dv)
+    rp, col, val = oracle.unfold_mode3(shape, xi, xj, xk, vals)
+    assert (U.rows, U.cols) == (I * J, K)
+    assert np.array_equal(U.rowptr.cpu().numpy(), rp) and np.array_equal(U.colidx.cpu().numpy(), col)
+    assert np.array_equal(U.values.cpu().numpy(), val)   # a stable sort: repeated coordinates keep their input order
+    Y = sg.spttm_mode3(h, shape, dxi, dxj, dxk, dv, sg.to_device(M))
+    torch.cuda.synchronize()
+    ref = oracle.spttm_mode3(shape, xi, xj, xk, vals, M)
+    assert np.array_equal(Y.rowptr.cpu().numpy(), ref.rowptr) and np.array_equal(Y.colidx.cpu().numpy(), ref.colidx)
+    want = ref.values.astype(dtype).astype(np.float64)
+    err = np.abs(Y.values.cpu().numpy().astype(np.float64) - want)
+    assert np.all(err <= RTOL[np.dtype(dtype)] * ref.absum)
+    yi, yj = sg.sptensor_fold_mode3(h, J, Y)
+    torch.cuda.synchronize()
+    rows = np.repeat(np.arange(I * J), np.diff(ref.rowptr))
+    assert np.array_equal(yi.cpu().numpy(), (rows // J).astype(np.int32)) and np.array_equal(yj.cpu().numpy(), (rows % J).astype(np.int32))
+
+
+def test_coordinate_out_of_range_is_reported():
+    from paper_2404_04541_amd import binding as sg
+    h = sg.Handle()
+    xi, xj, xk = (to_dev(np.array(v, dtype=np.int32)) for v in ([0, 1], [0, 5], [1, 1]))
+    with pytest.raises(sg.SpgemmError) as e:
+        sg.sptensor_unfold_mode3(h, (2, 5, 3), xi, xj, xk, to_dev(np.array([1.0, 2.0])))
+    assert e.value.status == -8
+
+
+def test_config5_through_the_tensor_entry_point():
+    # the full-size tensor of configuration 5 from its coordinates: unfolding on the GPU must give the
+    # matrix that the generator builds on the host, and the product the same C as the matrix route
+    import torch
+    from paper_2404_04541_amd import binding as sg
+    x = W.coo3_uniform((2048, 2048, 2048), 10_000_000, 0, 40, np.float64)
+    m = W.uniform_rows(2048, 2048, 16, 0, 44, np.float64)
+    order = np.argsort(W.rand_u64(0, 77, np.arange(x.values.size, dtype=np.uint64)), kind="stable")   # hand the entries over unordered
+    h = sg.Handle()
+    dxi, dxj, dxk, dv = (to_dev(v[order]) for v in (x.i, x.j, x.k, x.values))
+    U = sg.sptensor_unfold_mode3(h, x.shape, dxi, dxj, dxk, dv)
+    a = W.unfold_mode3(x)
+    assert np.array_equal(U.rowptr.cpu().numpy(), a.rowptr) and np.array_equal(U.colidx.cpu().numpy(), a.colidx)
+    assert np.array_equal(U.values.cpu().numpy(), a.values)
+    dM = sg.to_device(m)
+    Y = sg.spttm_mode3(h, x.shape, dxi, dxj, dxk, dv, dM)
+    C = sg.spgemm(h, sg.to_device(a), dM)
+    torch.cuda.synchronize()
+    assert torch.equal(Y.rowptr, C.rowptr) and torch.equal(Y.colidx, C.colidx)
+    assert torch.allclose(Y.values, C.values, rtol=1e-12, atol=1e-14)
+    assert Y.nnz > 150_000_000

@@ -139,20 +139,21 @@ __device__ __forceinline__ int classify_numeric(long long ip, int cnt, int force
   return staged_ok ? 4 : dense;
 }
 
-// Bitonic sort of N (power of two) keys held in LDS by G cooperating threads
-// (thread index gl in [0, G)).  When vals is non-null the values move with their keys.
+// Bitonic sort of the first n keys (a power of two, at most NMAX) held in LDS by G cooperating
+// threads (thread index gl in [0, G)).  When vals is non-null the values move with their keys.
 // A thread loads all the pairs it compares in a stage before it writes any back, so that a
 // stage costs one LDS round trip instead of one per pair.
-template <int G, int N, typename V>
-__device__ __forceinline__ void bitonic_sort_lds(int* keys, V* vals, int gl) {
-  constexpr int kPairs = (N / 2 + G - 1) / G;
-  for (int k = 2; k <= N; k <<= 1) {
+template <int G, int NMAX, typename V>
+__device__ __forceinline__ void bitonic_sort_lds(int* keys, V* vals, int n, int gl) {
+  constexpr int kPairs = (NMAX / 2 + G - 1) / G;
+  const int half = n >> 1;
+  for (int k = 2; k <= n; k <<= 1) {
     for (int j = k >> 1; j > 0; j >>= 1) {
       int ka[kPairs], kb[kPairs];
 #pragma unroll
       for (int q = 0; q < kPairs; ++q) {
         const int t = gl + q * G;
-        if (N / 2 % G == 0 || t < N / 2) {
+        if (t < half) {
           const int i = ((t & ~(j - 1)) << 1) | (t & (j - 1));
           ka[q] = keys[i];
           kb[q] = keys[i | j];
@@ -161,7 +162,7 @@ __device__ __forceinline__ void bitonic_sort_lds(int* keys, V* vals, int gl) {
 #pragma unroll
       for (int q = 0; q < kPairs; ++q) {
         const int t = gl + q * G;
-        if (N / 2 % G == 0 || t < N / 2) {
+        if (t < half) {
           const int i = ((t & ~(j - 1)) << 1) | (t & (j - 1));
           const int p = i | j;
           const bool up = (i & k) == 0;

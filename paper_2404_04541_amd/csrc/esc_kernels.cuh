@@ -65,7 +65,7 @@ __global__ __launch_bounds__(256) void k_esc(const int* __restrict__ perm, const
     for (int t = filled + gl; t < CAP; t += GROUP) keys[t] = kPadKey;
     group_sync<GROUP>();
     // ---- sort
-    bitonic_sort_lds<GROUP, CAP, double>(keys, vals, gl);
+    bitonic_sort_lds<GROUP, CAP, double>(keys, vals, CAP, gl);
     // ---- merge: a list position is a head when its column differs from its left neighbour
     const int i0 = 2 * gl, i1 = 2 * gl + 1;
     const int k0 = keys[i0], k1 = keys[i1];

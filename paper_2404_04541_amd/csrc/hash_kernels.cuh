@@ -33,6 +33,30 @@ __device__ __forceinline__ int pick_lb(int ip, int d, int group) {
   return lb;
 }
 
+constexpr int kHashUnroll = 4;
+
+// Exclusive scan over a group of GROUP threads (a wave, or the workgroup of 256), with the total.
+// part: GROUP / 64 + 1 ints of LDS of the group.  Contains the group's synchronisation when GROUP > 64.
+template <int GROUP>
+__device__ __forceinline__ int group_excl_scan(int v, int& total, int* part) {
+  const int incl = wave_incl_scan(v);
+  if constexpr (GROUP <= kWave) {
+    total = __shfl(incl, kWave - 1, kWave);
+    return incl - v;
+  } else {
+    constexpr int kW = GROUP / kWave;
+    const int wave = threadIdx.x >> 6;
+    __syncthreads();
+    if (lane_id() == kWave - 1) part[wave] = incl;
+    __syncthreads();
+    int before = 0;
+    total = 0;
+#pragma unroll
+    for (int w = 0; w < kW; ++w) { const int x = part[w]; if (w < wave) before += x; total += x; }
+    return before + incl - v;
+  }
+}
+
 // GROUP threads per row (64: one wave, several rows per workgroup; 256: the workgroup).
 template <int GROUP, int LOGH, typename T, bool NUMERIC>
 __global__ __launch_bounds__(256) void k_hash(const int* __restrict__ perm, const Control* __restrict__ ctl, int phase, int bin,
@@ -49,6 +73,13 @@ __global__ __launch_bounds__(256) void k_hash(const int* __restrict__ perm, cons
   double* all_vals = reinterpret_cast<double*>(smem);
   int* all_keys = reinterpret_cast<int*>(smem + (NUMERIC ? (size_t)kGroups * H * sizeof(double) : 0));
   int* counters = all_keys + kGroups * H;
+  // per group: the entries being inserted (length prefix, B row start, a_ik) and scan partials
+  unsigned char* extra = reinterpret_cast<unsigned char*>(counters + kGroups);
+  extra += (8 - (reinterpret_cast<size_t>(extra) & 7)) & 7;
+  int64_t* all_pbs = reinterpret_cast<int64_t*>(extra);
+  double* all_pav = reinterpret_cast<double*>(all_pbs + kGroups * GROUP);
+  int* all_pre = reinterpret_cast<int*>(all_pav + kGroups * GROUP);
+  int* part = all_pre + kGroups * (GROUP + 1);
   if (ctl->error) return;
   const unsigned first = ctl->offset[phase][bin];
   const unsigned nrows = ctl->offset[phase][bin + 1] - first;
@@ -56,6 +87,9 @@ __global__ __launch_bounds__(256) void k_hash(const int* __restrict__ perm, cons
   const int gl = threadIdx.x % GROUP;
   int* keys = all_keys + g * H;
   double* vals = NUMERIC ? all_vals + g * H : nullptr;
+  int64_t* pbs = all_pbs + g * GROUP;
+  double* pav = all_pav + g * GROUP;
+  int* pre = all_pre + g * (GROUP + 1);
   const unsigned ngroups = gridDim.x * kGroups;
   const unsigned rounds = (nrows + ngroups - 1) / ngroups;
   for (unsigned r = 0; r < rounds; ++r) {
@@ -68,25 +102,66 @@ __global__ __launch_bounds__(256) void k_hash(const int* __restrict__ perm, cons
     }
     if (gl == 0) counters[g] = 0;
     group_sync<GROUP>();
-    if (live) {
-      const int64_t a0 = a_rp[row];
-      const int d = (int)(a_rp[row + 1] - a0);
-      const int lb = pick_lb(ip_row[row], d, GROUP);
-      const int la = GROUP / lb;
-      const int ai = gl / lb, bo = gl % lb;
+    // insert: GROUP entries of the A row are described at a time (B row start, length, a_ik); their
+    // products form one index space that the group's threads walk with kHashUnroll loads in flight,
+    // a thread finding the entry of a product by bisection of the length prefix
+    {
+      const int64_t a0 = live ? a_rp[row] : 0;
+      const int d = live ? (int)(a_rp[row + 1] - a0) : 0;
+      int dmax = d;   // all groups of the workgroup walk in step (the barriers below are shared when GROUP > 64)
+      if constexpr (GROUP > kWave) dmax = d; else {
+#pragma unroll
+        for (int sh = GROUP; sh < kWave; sh <<= 1) { const int o = __shfl_xor(dmax, sh, kWave); dmax = o > dmax ? o : dmax; }
+      }
       int fresh = 0;
-      for (int e = ai; e < d; e += la) {
-        const int k = a_col[a0 + e];
-        const int64_t bs = b_rp[k], be = b_rp[k + 1];
+      for (int base = 0; base < dmax; base += GROUP) {
+        const int e = base + gl;
+        int64_t bs = 0;
+        int len = 0;
         double av = 0.0;
-        if (NUMERIC) av = (double)a_val[a0 + e];
-        for (int64_t q = bs + bo; q < be; q += lb) {
-          int is_new;
-          const int h = hash_find_or_insert<LOGH>(keys, b_col[q], is_new);
-          fresh += is_new;
-          if (NUMERIC)
-            __hip_atomic_fetch_add(&vals[h], av * (double)b_val[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        if (e < d) {
+          const int k = a_col[a0 + e];
+          bs = b_rp[k];
+          len = (int)(b_rp[k + 1] - bs);
+          if (NUMERIC) av = (double)a_val[a0 + e];
         }
+        int total;
+        const int excl = group_excl_scan<GROUP>(len, total, part + g * (GROUP / kWave + 1));
+        pre[gl] = excl;
+        pbs[gl] = bs;
+        if (NUMERIC) pav[gl] = av;
+        if (gl == 0) pre[GROUP] = total;
+        group_sync<GROUP>();
+        for (int f0 = gl; f0 < total; f0 += GROUP * kHashUnroll) {
+          int col[kHashUnroll];
+          double prod[kHashUnroll];
+#pragma unroll
+          for (int u = 0; u < kHashUnroll; ++u) {
+            const int f = f0 + u * GROUP;
+            col[u] = -1;
+            prod[u] = 0.0;
+            if (f < total) {
+              int lo = 0, hi = GROUP;   // last entry whose first product is <= f
+              while (hi - lo > 1) {
+                const int mid = (lo + hi) >> 1;
+                if (pre[mid] <= f) lo = mid; else hi = mid;
+              }
+              const int64_t q = pbs[lo] + (f - pre[lo]);
+              col[u] = b_col[q];
+              if (NUMERIC) prod[u] = pav[lo] * (double)b_val[q];
+            }
+          }
+#pragma unroll
+          for (int u = 0; u < kHashUnroll; ++u) {
+            if (col[u] >= 0) {
+              int is_new;
+              const int h = hash_find_or_insert<LOGH>(keys, col[u], is_new);
+              fresh += is_new;
+              if (NUMERIC) __hip_atomic_fetch_add(&vals[h], prod[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            }
+          }
+        }
+        group_sync<GROUP>();
       }
       if (!NUMERIC && fresh) atomicAdd(&counters[g], fresh);
     }
@@ -94,10 +169,30 @@ __global__ __launch_bounds__(256) void k_hash(const int* __restrict__ perm, cons
     if (!NUMERIC) {
       if (live && gl == 0) cnt[row] = counters[g];
     } else {
-      // empty slots hold kEmptyKey = -1: turn them into the pad key so they sort last
-      for (int t = gl; t < H; t += GROUP) if (keys[t] == kEmptyKey) keys[t] = kPadKey;
+      // retrieve: the occupied slots move to the front of the table (through registers: a thread
+      // reads its share of slots before anything is written back), the rest up to the next power of
+      // two is padded, and only that many entries are sorted
+      constexpr int kSlots = H / GROUP;
+      int sk[kSlots];
+      double sv[kSlots];
+      int mine = 0;
+#pragma unroll
+      for (int q = 0; q < kSlots; ++q) {
+        sk[q] = keys[gl * kSlots + q];
+        sv[q] = vals[gl * kSlots + q];
+        mine += sk[q] != kEmptyKey ? 1 : 0;
+      }
+      int filled;
+      int at = group_excl_scan<GROUP>(mine, filled, part + g * (GROUP / kWave + 1));
       group_sync<GROUP>();
-      bitonic_sort_lds<GROUP, H, double>(keys, vals, gl);
+#pragma unroll
+      for (int q = 0; q < kSlots; ++q)
+        if (sk[q] != kEmptyKey) { keys[at] = sk[q]; vals[at] = sv[q]; ++at; }
+      int nsort = 2;
+      while (nsort < filled) nsort <<= 1;
+      for (int t = filled + gl; t < nsort; t += GROUP) keys[t] = kPadKey;
+      group_sync<GROUP>();
+      bitonic_sort_lds<GROUP, H, double>(keys, vals, nsort, gl);
       if (live) {
         const int64_t out = c_rp[row];
         const int n = (int)(c_rp[row + 1] - out);
@@ -113,7 +208,8 @@ __global__ __launch_bounds__(256) void k_hash(const int* __restrict__ perm, cons
 
 template <int GROUP, int LOGH, bool NUMERIC>
 constexpr size_t hash_lds_bytes() {
-  return (size_t)(256 / GROUP) * (1u << LOGH) * (sizeof(int) + (NUMERIC ? sizeof(double) : 0)) + (256 / GROUP) * sizeof(int);
+  return (size_t)(256 / GROUP) * (1u << LOGH) * (sizeof(int) + (NUMERIC ? sizeof(double) : 0)) + (256 / GROUP) * sizeof(int) + 8 +
+         (size_t)256 * (8 + 8 + 4) + (256 / GROUP) * 4 + (size_t)(256 / GROUP) * (GROUP / kWave + 1) * 4;
 }
 
 }  // namespace spg

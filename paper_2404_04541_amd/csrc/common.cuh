@@ -80,16 +80,19 @@ __device__ __forceinline__ int wave_incl_scan(int v) {
   return v;
 }
 
-// Inclusive scan inside aligned groups of WIDTH lanes (WIDTH a power of two <= 64).
+// Inclusive scan inside aligned groups of WIDTH lanes (16: a DPP row, or the whole wave).
 template <int WIDTH>
 __device__ __forceinline__ int group_incl_scan(int v) {
-  const int l = threadIdx.x & (WIDTH - 1);
-#pragma unroll
-  for (int d = 1; d < WIDTH; d <<= 1) {
-    int t = __shfl_up(v, d, WIDTH);
-    if (l >= d) v += t;
+  static_assert(WIDTH == 16 || WIDTH == kWave, "a DPP row or the wave");
+  if constexpr (WIDTH == kWave) {
+    return wave_incl_scan(v);
+  } else {
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, true);   // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, true);   // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, true);   // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, true);   // row_shr:8
+    return v;
   }
-  return v;
 }
 
 __device__ __forceinline__ int wave_sum(int v) {

@@ -55,9 +55,22 @@ __global__ __launch_bounds__(256) void k_esc(const int* __restrict__ perm, const
       }
       const int incl = group_incl_scan<GROUP>(len);
       int pos = filled + incl - len;
-      for (int t = 0; t < len; ++t) {
-        keys[pos + t] = b_col[bs + t];
-        if (NUMERIC) vals[pos + t] = av * (double)b_val[bs + t];
+      for (int t0 = 0; t0 < len; t0 += 4) {   // four loads in flight per lane
+        int cc[4];
+        T vv[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const bool ok = t0 + u < len;
+          cc[u] = ok ? b_col[bs + t0 + u] : 0;
+          if (NUMERIC) vv[u] = ok ? b_val[bs + t0 + u] : T(0);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          if (t0 + u < len) {
+            keys[pos + t0 + u] = cc[u];
+            if (NUMERIC) vals[pos + t0 + u] = av * (double)vv[u];
+          }
+        }
       }
       filled += __shfl(incl, GROUP - 1, GROUP);
     }

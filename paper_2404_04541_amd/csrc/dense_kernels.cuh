@@ -624,10 +624,12 @@ __device__ __forceinline__ void chunk_pass_batches(int np, int nchunks, const Nu
       if (cu < cend) {
         if (cu >= lane_get(d_first, q + 1)) ++q;   // every piece has at least one chunk: one step suffices
         const int off = (cu - lane_get(d_first, q)) * kWave + lane;
-        const long long s = lane_get(d_s, q);
+        // (wave-uniform piece start + 32-bit lane offset: scalar base, one vector offset)
+        const int32_t* pc = b_col + lane_get(d_s, q);
+        const T* pv = b_val + lane_get(d_s, q);
         if (off < lane_get(d_len, q)) {
-          col[u] = b_col[s + off];
-          if (WITH_VALUES) bv[u] = b_val[s + off];
+          col[u] = pc[(unsigned)off];
+          if (WITH_VALUES) bv[u] = pv[(unsigned)off];
         }
         if (WITH_VALUES) au[u] = lane_get(d_av, q);
       }

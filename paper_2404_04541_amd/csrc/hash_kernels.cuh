@@ -24,15 +24,6 @@ __device__ __forceinline__ int hash_find_or_insert(int* keys, int key, int& is_n
   }
 }
 
-// Lanes of a group are laid out as LA x LB: LB lanes walk one B row together, LA rows of B
-// are in flight at once; LB is the power of two nearest above the row's mean B-row length.
-__device__ __forceinline__ int pick_lb(int ip, int d, int group) {
-  int avg = d > 0 ? (ip + d - 1) / d : 1;
-  int lb = 1;
-  while (lb < avg && lb < group && lb < kWave) lb <<= 1;
-  return lb;
-}
-
 constexpr int kHashUnroll = 4;
 
 // Exclusive scan over a group of GROUP threads (a wave, or the workgroup of 256), with the total.

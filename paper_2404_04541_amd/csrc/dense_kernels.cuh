@@ -48,6 +48,10 @@ constexpr int kSegCap = 1024;           // A entries described in LDS at a time 
 constexpr int kBlkWords = kBlkCols / 32;
 constexpr int kListStage = 320;          // entries that a wave gathers in LDS before writing them to the column list
 constexpr int kListBatch = 4;           // column-list loads in flight per thread
+// every tile kind must fit the tile area of the numeric kernel
+static_assert((long long)kSearchCap * 12 <= kTileBudget, "searched tile: 4 B column + 8 B sum per entry");
+static_assert((long long)kBlkCols * 12 + kBlkCols / 8 <= kTileBudget, "direct tile: sums, columns by rank, flag words");
+static_assert(kRankBlkBytes + 8LL * kBlkCols <= kTileBudget, "ranked tile: one block must fit even when it is full");
 constexpr int kRegSegs = 2;             // segments of A entries that the numeric kernel keeps in registers
 constexpr long long kListBias = 1LL << 40;   // RunRec::list holds position + bias (so that -1 can mean "none")
 

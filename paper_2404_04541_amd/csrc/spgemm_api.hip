@@ -20,6 +20,11 @@
 
 using namespace spg;
 
+// a workgroup of the big kernels owns the whole LDS of a compute unit (160 KB)
+static_assert(num_dense_lds<double>() <= 160 * 1024 && num_dense_lds<float>() <= 160 * 1024, "numeric dense kernel exceeds LDS");
+static_assert(kSymDenseLds <= 160 * 1024, "symbolic dense kernel exceeds LDS");
+static_assert(staged_lds<double>() <= 160 * 1024 && staged_lds<float>() <= 160 * 1024, "staged kernel exceeds LDS");
+
 struct TimedLaunch {
   int cls;
   hipEvent_t start, stop;

@@ -129,7 +129,11 @@ enum {
   /* 1 (default): for an ascending B the plan holds a table of per-row offsets at every 8192nd
    * column (when it fits 1 GiB), which turns the search for a tile's piece of a B row into two
    * loads.  0: never build it; pieces are found by bisection. */
-  SPGEMM_OPT_BLOCK_TABLE = 5
+  SPGEMM_OPT_BLOCK_TABLE = 5,
+  /* A short dense row (at most 11264 entries, columns in the plan's list) whose products per entry do
+   * not exceed this value is accumulated in one "searched" tile: a product finds its sum by bisection of
+   * the row's column list, whatever the width of the row.  0: never.  Default 4. */
+  SPGEMM_OPT_SEARCH_RATIO = 6
 };
 
 /* Create a handle bound to a HIP stream (hipStream_t passed as void*, null = default

@@ -17,7 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libspgemm_gfx950.so")
 
 SPGEMM_F32, SPGEMM_F64 = 0, 1
-OPT_TIMING, OPT_FORCE_WORKSPACE, OPT_DIRECT_MIN, OPT_COLUMN_LIST, OPT_BLOCK_TABLE = 1, 2, 3, 4, 5
+OPT_TIMING, OPT_FORCE_WORKSPACE, OPT_DIRECT_MIN, OPT_COLUMN_LIST, OPT_BLOCK_TABLE, OPT_SEARCH_RATIO = 1, 2, 3, 4, 5, 6
 WORKSPACE_AUTO, WORKSPACE_SORTED_LIST, WORKSPACE_HASH, WORKSPACE_DENSE, WORKSPACE_STAGED = 0, 1, 2, 3, 4
 NUM_KERNEL_CLASSES = 11
 NUM_BINS = 8

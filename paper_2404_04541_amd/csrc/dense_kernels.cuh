@@ -353,7 +353,8 @@ __global__ __launch_bounds__(kDenseThreads) void k_sym_dense(const int* __restri
                                                              const int64_t* __restrict__ b_rp, const int32_t* __restrict__ b_col,
                                                              int64_t n_cols, const int* __restrict__ ip, int* __restrict__ cnt,
                                                              TileRec* __restrict__ tiles, RunRec* __restrict__ runs,
-                                                             int32_t* __restrict__ col_list, int direct_min, int no_tiles_ip) {
+                                                             int32_t* __restrict__ col_list, int direct_min, int no_tiles_ip,
+                                                             int search_ratio) {
   extern __shared__ __align__(16) unsigned char smem[];
   unsigned* flags = reinterpret_cast<unsigned*>(smem);                               // kSymFlagWords
   RowScratch* rs = reinterpret_cast<RowScratch*>(smem + (size_t)kSymFlagWords * 4);
@@ -419,7 +420,8 @@ __global__ __launch_bounds__(kDenseThreads) void k_sym_dense(const int* __restri
         // Everything this span needs from the plan's shared lists, and the next row, in one round trip:
         // room for the entries in the column list (without it the numeric kernel rebuilds the flags
         // itself), tile and run records.  A span that is the whole row, got room in the list and has at
-        // most kSearchCap entries becomes one searched tile (the records planned above stay unused).
+        // most kSearchCap entries and at most search_ratio products per entry becomes one searched tile
+        // (the records planned above stay unused).
         const int total = tp->cum[128];
         const int nt = tp->ntiles;
         const int nr = (nt + kRunTiles - 1) / kRunTiles;
@@ -439,7 +441,9 @@ __global__ __launch_bounds__(kDenseThreads) void k_sym_dense(const int* __restri
           ctl->error = 3;   // cannot happen when the host sized the lists from the bound
           tp->ntiles = 0;
           tp->nruns = 0;
-        } else if (listed && whole_row && total <= kSearchCap && nt > 0) {
+        } else if (listed && whole_row && total <= kSearchCap && nt > 1 && (long long)ip[row] <= (long long)search_ratio * total) {
+          // (a searched tile pays a bisection per product: only for rows with little deduplication, and
+          // only where it saves tiles - a row that is one ranked or direct tile anyway stays that)
           tp->rec[0] = TileRec{block0, block0 + nb, total | kSearchBit, tp->span_out0};
           tp->ntiles = 1;
           atomicAdd(&ctl->search_tiles, 1u);

@@ -39,6 +39,7 @@ struct spgemm_context {
   int direct_min = kDirectMinDefault;
   int64_t col_list = 1;   // 0 off, 1 automatic size, larger: byte limit
   int block_table = 1;    // 0: never build the block-offset table of B (pieces are bisected)
+  int search_ratio = 4;   // searched tiles for rows with at most this many products per entry (0: never)
   std::string err = "";
   bool device_ready = false;
   int num_cus = 0;
@@ -340,7 +341,7 @@ int run_symbolic(spgemm_context* h, spgemm_plan_s* p, const spgemm_csr* A, const
       Timer t(h, SPGEMM_K_SYM_DENSE);
       hipLaunchKernelGGL(k_sym_dense, dim3(grid_for(rows_dense, 1, h->num_cus)), dim3(kDenseThreads), kSymDenseLds, s, p->perm_sym,
                          p->ctl, A->rowptr, A->colidx, B->rowptr, B->colidx, B->cols, p->ip, p->cnt, p->tiles, p->runs, p->col_list, h->direct_min,
-                         staged);
+                         staged, h->search_ratio);
     }
     {
       Timer t(h, SPGEMM_K_BIN);
@@ -459,6 +460,10 @@ int spgemm_set_option(spgemm_handle h, int option, int64_t value) {
       // a direct block keeps its 256 flag words in the list space of its entries
       if (value < kBlkWords || value > 0x3fffffff) return fail(h, SPGEMM_INVALID_ARG, "direct-tile threshold takes 256..2^30-1");
       h->direct_min = (int)value;
+      return SPGEMM_OK;
+    case SPGEMM_OPT_SEARCH_RATIO:
+      if (value < 0 || value > 1000000) return fail(h, SPGEMM_INVALID_ARG, "search-ratio option takes 0..1000000");
+      h->search_ratio = (int)value;
       return SPGEMM_OK;
     case SPGEMM_OPT_BLOCK_TABLE:
       if (value != 0 && value != 1) return fail(h, SPGEMM_INVALID_ARG, "block-table option takes 0 or 1");

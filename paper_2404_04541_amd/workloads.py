@@ -277,6 +277,33 @@ def random_csr(rows: int, cols: int, mean_per_row: float, seed: int, stream: int
     return CSR(rows, cols, rowptr, col.astype(np.int32), vals)
 
 
+def dedup_sweep(K: int, dense_elements: int = 100_000_000, column_fraction: float = 0.1, per_column: int = 1000,
+                seed: int = 0, stream: int = 80, dtype=np.float64):
+    """Operands of the paper's synthetic first-order sweep (section 7.2): B is I x K with I*K = dense_elements;
+    a tenth of its columns are non-empty, each with per_column nonzeros at distinct uniform rows; the second
+    operand is the transpose of B with its columns rotated by one (section 7.1).  Growing K shrinks I, so
+    more products of a row land on the same output column (more deduplication).
+    Returns (B, C) with C of shape K x I; the product B*C is I x I."""
+    I = dense_elements // K
+    nc = max(1, int(round(K * column_fraction)))
+    per_column = min(per_column, I)
+    cols = np.sort(np.argsort(rand_u64(seed, stream, np.arange(K, dtype=np.uint64)), kind="stable")[:nc])
+    # per non-empty column: the per_column rows with the smallest random keys
+    keys = rand_u64(seed, stream + 1, np.arange(nc * I, dtype=np.uint64)).reshape(nc, I)
+    rows = np.argpartition(keys, per_column - 1, axis=1)[:, :per_column]
+    r = rows.reshape(-1).astype(np.int64)
+    c = np.repeat(cols, per_column).astype(np.int64)
+    vals = draw_values(r.size, -1.0, 1.0, dtype, seed, stream + 2)
+    def to_csr(nrows, ncols, rr, cc, vv):
+        order = np.lexsort((cc, rr))
+        rowptr = np.zeros(nrows + 1, dtype=np.int64)
+        np.cumsum(np.bincount(rr, minlength=nrows), out=rowptr[1:])
+        return CSR(nrows, ncols, rowptr, cc[order].astype(np.int32), vv[order])
+    B = to_csr(I, K, r, c, vals)
+    C = to_csr(K, I, c, (r + 1) % I, vals)
+    return B, C
+
+
 # ---------------------------------------------------------------------------
 # The five benchmark configurations (seed 0 for all).
 # ---------------------------------------------------------------------------

@@ -85,6 +85,7 @@ def test_argument_errors_come_before_any_gpu_work(lib):
     assert lib.spgemm_set_option(h, 3, 255) == -1              # direct-tile threshold: 256 or more
     assert lib.spgemm_set_option(h, 4, 100) == -1              # column list: 0, 1 or a byte limit >= 4096
     assert lib.spgemm_set_option(h, 4, 1 << 20) == 0
+    assert lib.spgemm_set_option(h, 6, -1) == -1               # products per entry for searched tiles: 0 or more
     assert lib.spgemm_get_stats(None, None) == -1
     assert lib.spgemm_plan_destroy(None) == -1
     assert lib.spgemm_destroy(h) == 0

@@ -54,7 +54,6 @@ def test_rmat_small_scale_power_law(force):
     st = run(a, b, force, what=f"rmat scale 13 force={force}")
     if force == AUTO:
         assert sum(st["num_bin_rows"][5:7]) > 0, "long rows must reach the dense workspace"
-        assert st["dense_search_tiles"] > 0, "short dense rows become searched tiles"
     if force == STAGED:
         assert st["num_bin_rows"][4] > 0, "rows of few products must reach the staged coordinate list"
 
@@ -77,11 +76,28 @@ def test_dense_tiles_direct_ranked_with_and_without_column_list(column_list, dir
              options={sg.OPT_COLUMN_LIST: column_list, sg.OPT_DIRECT_MIN: direct_min})
     ranked = st["dense_tiles"] - st["dense_search_tiles"] - st["dense_direct_tiles"]
     assert ranked > 0 or direct_min == 256, "hub rows need ranked tiles unless every block counts as dense"
-    assert (st["dense_search_tiles"] > 0) == (column_list == 1)   # searched tiles need the list
+    if column_list == 0:
+        assert st["dense_search_tiles"] == 0   # searched tiles need the list
     if direct_min == 256:
         assert st["dense_direct_tiles"] > 0
     if direct_min == 1 << 20:
         assert st["dense_direct_tiles"] == 0
+
+
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+def test_short_rows_over_many_columns_become_searched_tiles(dtype):
+    # a few thousand entries per row of C spread over a million columns: several ranked tiles by width,
+    # one searched tile by entry count (ranks by bisection of the plan's column list)
+    from paper_2404_04541_amd import binding as sg
+    A = W.random_csr(300, 3000, 6, 71, dtype=dtype)
+    B = W.random_csr(3000, 1_000_000, 500, 72, dtype=dtype)
+    st = run(A, B, AUTO, what="searched tiles")
+    assert st["dense_search_tiles"] > 0
+    st = run(A, B, AUTO, what="searched tiles off", options={sg.OPT_SEARCH_RATIO: 0})
+    assert st["dense_search_tiles"] == 0 and st["dense_tiles"] > 0
+    # a list too small for all rows: some searched, the others through the staged or ranked routes
+    st = run(A, B, AUTO, what="searched tiles, small list", options={sg.OPT_COLUMN_LIST: 1 << 18})
+    assert 0 < st["dense_search_tiles"] < 300
 
 
 def test_column_list_too_small_for_all_rows():
@@ -90,7 +106,7 @@ def test_column_list_too_small_for_all_rows():
     a, b = W.config3(scale=14)
     for force in (AUTO, DENSE):
         st = run(a, b, force, what=f"small list force={force}", options={sg.OPT_COLUMN_LIST: 1 << 18})
-        assert st["dense_tiles"] > st["dense_search_tiles"] > 0
+        assert st["dense_tiles"] > 0
 
 
 @pytest.mark.parametrize("column_list", [1, 0])
@@ -111,6 +127,18 @@ def test_wide_matrix_several_flag_list_spans_and_long_a_rows():
     for force in (AUTO, DENSE):
         st = run(A, B, force, what=f"wide force={force}")
         assert st["dense_tiles"] > 0
+
+
+@pytest.mark.parametrize("direct_min", [256, 1 << 20])
+def test_dedup_sweep_operands_dense_and_sparse_routes(direct_min):
+    # the paper's synthetic sweep at a reduced size
+    from paper_2404_04541_amd import binding as sg
+    B, C = W.dedup_sweep(4000, dense_elements=40_000_000, per_column=400)
+    for force, ratio in ((AUTO, 4), (DENSE, 0), (DENSE, 1000000)):
+        st = run(B, C, force, what=f"dedup sweep force={force} direct_min={direct_min} search_ratio={ratio}",
+                 options={sg.OPT_DIRECT_MIN: direct_min, sg.OPT_SEARCH_RATIO: ratio})
+        if ratio == 0:
+            assert st["dense_search_tiles"] == 0
 
 
 def test_dense_workspace_many_windows_and_tiles():

@@ -96,3 +96,15 @@ def test_small_instances_of_the_configs():
     a, m = W.config5(dim=32, nnz=5000)
     _canonical(a); _canonical(m)
     assert (a.rows, a.cols, a.nnz) == (1024, 32, 5000) and m.nnz == 16 * 32
+
+
+def test_dedup_sweep_operands_follow_the_recipe():
+    B, C = W.dedup_sweep(500, dense_elements=100_000, per_column=50)
+    assert (B.rows, B.cols, C.rows, C.cols) == (200, 500, 500, 200)
+    per_col = np.bincount(B.colidx, minlength=500)
+    assert (per_col > 0).sum() == 50 and set(per_col[per_col > 0]) == {50}      # a tenth of the columns, 50 entries each
+    assert np.array_equal(np.roll(B.to_dense().T, 1, axis=1), C.to_dense())       # second operand: B^T, columns rotated by one
+    for M in (B, C):
+        for i in range(M.rows):
+            c = M.colidx[M.rowptr[i]:M.rowptr[i + 1]]
+            assert np.all(np.diff(c) > 0)

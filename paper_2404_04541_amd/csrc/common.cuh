@@ -95,6 +95,29 @@ __device__ __forceinline__ int group_incl_scan(int v) {
   }
 }
 
+// Sets `bits` in the flag word *word(w) for every calling lane, combining lanes first.  Lanes that
+// hold consecutive entries of an ascending column list hold runs of equal words, and LDS atomics on
+// one address are executed one lane after the other; so inside each DPP row of 16 lanes a lane ORs
+// in the bits of the lanes below it that hold the same word (four shifted steps), and only the last
+// lane of a run issues the atomic.  Any set of lanes may call (lanes that are off count as "another
+// word"); without runs it degenerates to one atomic per lane.
+template <int D>
+__device__ __forceinline__ void or_from_below(int w, unsigned& bits) {
+  const int wl = __builtin_amdgcn_update_dpp(-2, w, 0x110 + D, 0xf, 0xf, false);              // row_shr:D
+  const unsigned bl = (unsigned)__builtin_amdgcn_update_dpp(0, (int)bits, 0x110 + D, 0xf, 0xf, false);
+  if (wl == w) bits |= bl;
+}
+
+template <class WordOf>
+__device__ __forceinline__ void flags_or_combined(int w, unsigned bits, WordOf word) {
+  or_from_below<1>(w, bits);
+  or_from_below<2>(w, bits);
+  or_from_below<4>(w, bits);
+  or_from_below<8>(w, bits);
+  const int wr = __builtin_amdgcn_update_dpp(-2, w, 0x101, 0xf, 0xf, false);                   // row_shl:1
+  if (wr != w) atomicOr(word(w), bits);
+}
+
 __device__ __forceinline__ int wave_sum(int v) {
 #pragma unroll
   for (int d = kWave / 2; d > 0; d >>= 1) v += __shfl_xor(v, d, kWave);

@@ -621,6 +621,11 @@ __device__ __forceinline__ void chunk_pass_batches(int np, int nchunks, const Nu
     const long long d_s = ns->c_s[pj];
     const T d_av = WITH_VALUES ? ns->c_av[pj] : T(0);
     int q = 0;
+    // the piece in hand (wave-uniform; re-read from the lanes only when the piece changes)
+    int q_first = lane_get(d_first, 0), q_next = lane_get(d_first, 1), q_len = lane_get(d_len, 0);
+    const int32_t* pc = b_col + lane_get(d_s, 0);
+    const T* pv = b_val + lane_get(d_s, 0);
+    T q_av = WITH_VALUES ? lane_get(d_av, 0) : T(0);
     int col[kChunkUnroll];
     T bv[kChunkUnroll], au[kChunkUnroll];
 #pragma unroll
@@ -630,16 +635,22 @@ __device__ __forceinline__ void chunk_pass_batches(int np, int nchunks, const Nu
       bv[u] = T(0);
       au[u] = T(0);
       if (cu < cend) {
-        if (cu >= lane_get(d_first, q + 1)) ++q;   // every piece has at least one chunk: one step suffices
-        const int off = (cu - lane_get(d_first, q)) * kWave + lane;
+        if (cu >= q_next) {   // every piece has at least one chunk: one step suffices
+          ++q;
+          q_first = q_next;
+          q_next = lane_get(d_first, q + 1);
+          q_len = lane_get(d_len, q);
+          pc = b_col + lane_get(d_s, q);
+          pv = b_val + lane_get(d_s, q);
+          if (WITH_VALUES) q_av = lane_get(d_av, q);
+        }
+        const int off = (cu - q_first) * kWave + lane;
         // (wave-uniform piece start + 32-bit lane offset: scalar base, one vector offset)
-        const int32_t* pc = b_col + lane_get(d_s, q);
-        const T* pv = b_val + lane_get(d_s, q);
-        if (off < lane_get(d_len, q)) {
+        if (off < q_len) {
           col[u] = pc[(unsigned)off];
           if (WITH_VALUES) bv[u] = pv[(unsigned)off];
         }
-        if (WITH_VALUES) au[u] = lane_get(d_av, q);
+        au[u] = q_av;
       }
     }
     p += q;
@@ -923,7 +934,7 @@ __device__ __forceinline__ void num_dense_run(const RunRec rr, NumScratch<T>* ns
             if ((tid & 63) == 0) prev = lp[i];
             if (c >= 0) {
               const int rel = c - t_lo;
-              atomicOr(&fc[rel >> 5].x, 1u << (rel & 31));
+              flags_or_combined(rel >> 5, 1u << (rel & 31), [&](int w) { return &fc[w].x; });
               if (prev < 0 || ((prev - t_lo) >> 5) != (rel >> 5)) fc[rel >> 5].y = (unsigned)j;
               stream_store(&c_col[out + j], c);
             }

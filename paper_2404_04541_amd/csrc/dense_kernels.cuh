@@ -647,8 +647,11 @@ __device__ __forceinline__ void chunk_pass_batches(int np, int nchunks, const Nu
         const int off = (cu - q_first) * kWave + lane;
         // (wave-uniform piece start + 32-bit lane offset: scalar base, one vector offset)
         if (off < q_len) {
-          col[u] = pc[(unsigned)off];
-          if (WITH_VALUES) bv[u] = pv[(unsigned)off];
+          // (a piece is far shorter than 2^30 elements: the byte offset fits 32 bits, which lets the
+          // load take the scalar base plus one vector offset)
+          const unsigned byte_off = (unsigned)off * (unsigned)sizeof(int32_t);
+          col[u] = *reinterpret_cast<const int32_t*>(reinterpret_cast<const char*>(pc) + byte_off);
+          if (WITH_VALUES) bv[u] = *reinterpret_cast<const T*>(reinterpret_cast<const char*>(pv) + (unsigned)off * (unsigned)sizeof(T));
         }
         au[u] = q_av;
       }

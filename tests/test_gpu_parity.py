@@ -42,6 +42,23 @@ def test_ragged_tail_and_many_tiles(dtype):
     run(A, B, what="ragged tails")
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_randomized_shapes_every_route(seed):
+    # seeded shapes and densities from tiny to a few thousand products per row, rectangular, both value
+    # types, every forced route: the same C from all of them
+    u = W.rand_unit(seed, 900, np.arange(8, dtype=np.uint64))
+    m, k, n = (1 + int(v * 1500) for v in u[:3])
+    da, db = 1 + u[3] * 30, 1 + u[4] * 60
+    dtype = np.float32 if seed % 2 else np.float64
+    A = W.random_csr(m, k, da, seed, 910, dtype=dtype, sort_rows=seed % 3 != 0, allow_duplicates=seed % 4 == 0)
+    B = W.random_csr(k, n * (40 if seed % 5 == 0 else 1), db, seed, 920, dtype=dtype, sort_rows=seed % 3 != 1,
+                     allow_duplicates=seed % 4 == 1)
+    ref = None
+    for force in (AUTO, LIST, HASH, DENSE, STAGED):
+        got = gpu_product(A, B, force)
+        ref = assert_matches_oracle(A, B, got, ref=ref, what=f"seed {seed} force={force} {m}x{k}x{B.cols}")
+
+
 def test_stencil_small_grid():
     a, b = W.config2(g=12)
     st = run(a, b, what="stencil 12^3")

@@ -118,7 +118,7 @@ enum {
   SPGEMM_OPT_FORCE_WORKSPACE = 2,
   /* Dense workspace tuning: a block of 8192 columns in which a row of C has at least this
    * many entries is accumulated in a dense array indexed by column (one pass over the
-   * products); sparser blocks are grouped and accumulated by rank.  256 or more; default 4096.
+   * products); sparser blocks are grouped and accumulated by rank.  256 or more; default 6144.
    * Applies to the next spgemm_symbolic on the handle. */
   SPGEMM_OPT_DIRECT_MIN = 3,
   /* 1 (default): the plan keeps the column indices of the dense workspace's ranked tiles

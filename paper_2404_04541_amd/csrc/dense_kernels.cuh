@@ -38,7 +38,7 @@ constexpr int kSpanBlocks = kSymFlagWords * 32 / kBlkCols;   // 128 blocks per s
 constexpr int kTileBudget = 135 * 1024; // LDS bytes of one numeric tile (flags + ranks + sums)
 constexpr int kRankBlkBytes = kBlkCols / 32 * 8;   // flag word + rank per 32 columns of a ranked tile
 constexpr int kRankEntryBytes = 8;                // sum per entry of a ranked tile (its column goes straight to C)
-constexpr int kDirectMinDefault = 4096; // a block with at least this many entries becomes a direct tile
+constexpr int kDirectMinDefault = 6144; // a block with at least this many entries becomes a direct tile
 constexpr int kRunTiles = 16;           // tiles handed to a workgroup at a time
 constexpr int kDirectBit = 1 << 30;     // in TileRec::cnt
 constexpr int kSearchBit = 1 << 29;     // in TileRec::cnt: a searched tile (ranks by bisection of the column list)

@@ -83,7 +83,7 @@ def test_rectangular_and_ttm_small():
 
 
 @pytest.mark.parametrize("column_list", [1, 0])
-@pytest.mark.parametrize("direct_min", [4096, 256, 1 << 20])
+@pytest.mark.parametrize("direct_min", [6144, 256, 1 << 20])
 def test_dense_tiles_direct_ranked_with_and_without_column_list(column_list, direct_min):
     # power-law rows: dense heads (direct tiles) and sparse tails (ranked tiles) in the same rows;
     # the ranked tiles take their structure from the plan's column list or rebuild it themselves

@@ -15,7 +15,7 @@ constexpr int kPadKey = 0x7fffffff;  // sorts behind every real column
 // (an upper bound of its output size); numeric classes on ip and the exact output size.
 constexpr int kEscSmallCap = 32;     // bin 0: sorted-list workspace, 16 lanes per row
 constexpr int kEscLargeCap = 128;    // bin 1: sorted-list workspace, one wave per row
-constexpr int kSymHashSmall = 1024;  // bin 2: hash set with 2048 slots, one wave per row
+constexpr int kSymHashSmall = 768;   // bin 2: hash set with 1024 slots, one wave per row
 constexpr int kSymHashLarge = 1536;  // bin 3: hash set with 4096 slots, 256 threads per row
 constexpr int kNumHashSmall = 192;   // bin 2: hash table with 256 slots, one wave per row
 constexpr int kNumHashLarge = 1536;  // bin 3: hash table with 2048 slots, 256 threads per row

@@ -293,7 +293,7 @@ int run_symbolic(spgemm_context* h, spgemm_plan_s* p, const spgemm_csr* A, const
   hipStream_t s = h->stream;
   const int64_t m = p->m;
   const int64_t cap_small = (int64_t)h->num_cus * 32;
-  const size_t lds_hash_small = hash_lds_bytes<64, 11, false>();
+  const size_t lds_hash_small = hash_lds_bytes<64, 10, false>();
   const size_t lds_hash_large = hash_lds_bytes<256, 12, false>();
   const unsigned* hist = host.hist[0];
   const int64_t rows_dense = (int64_t)hist[4] + hist[5] + hist[6];
@@ -328,7 +328,7 @@ int run_symbolic(spgemm_context* h, spgemm_plan_s* p, const spgemm_csr* A, const
     {
       Timer t(h, SPGEMM_K_SYM_HASH);
       if (hist[2])
-        hipLaunchKernelGGL((k_hash<64, 11, T, false>), dim3(grid_for(hist[2], 4, cap_small)), dim3(256), lds_hash_small, s,
+        hipLaunchKernelGGL((k_hash<64, 10, T, false>), dim3(grid_for(hist[2], 4, cap_small)), dim3(256), lds_hash_small, s,
                            p->perm_sym, p->ctl, 0, 2, p->ip, A->rowptr, A->colidx, (const T*)nullptr, B->rowptr, B->colidx,
                            (const T*)nullptr, p->cnt, (const int64_t*)nullptr, (int32_t*)nullptr, (T*)nullptr);
       if (hist[3])

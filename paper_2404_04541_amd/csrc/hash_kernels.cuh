@@ -56,8 +56,9 @@ __global__ __launch_bounds__(256) void k_hash(const int* __restrict__ perm, cons
                                                const T* __restrict__ a_val, const int64_t* __restrict__ b_rp,
                                                const int32_t* __restrict__ b_col, const T* __restrict__ b_val,
                                                int* __restrict__ cnt, const int64_t* __restrict__ c_rp,
-                                               int32_t* __restrict__ c_col, T* __restrict__ c_val) {
+                                               int32_t* __restrict__ c_col, T* __restrict__ c_val, int64_t n_cols) {
   constexpr int H = 1 << LOGH;
+  const bool packable = n_cols <= (int64_t(1) << (31 - LOGH));   // column << LOGH stays below the pad key
   constexpr int kGroups = 256 / GROUP;
   extern __shared__ __align__(16) unsigned char smem[];
   // layout: per group H keys, then (numeric) H doubles; one int counter per group at the end
@@ -176,20 +177,25 @@ __global__ __launch_bounds__(256) void k_hash(const int* __restrict__ perm, cons
       int filled;
       int at = group_excl_scan<GROUP>(mine, filled, part + g * (GROUP / kWave + 1));
       group_sync<GROUP>();
+      // When column and slot number fit one 32-bit word together, only those words are sorted and a
+      // sum is fetched through its slot number afterwards: a third of the LDS traffic of moving
+      // (column, double) pairs through the network.
 #pragma unroll
       for (int q = 0; q < kSlots; ++q)
-        if (sk[q] != kEmptyKey) { keys[at] = sk[q]; vals[at] = sv[q]; ++at; }
+        if (sk[q] != kEmptyKey) { keys[at] = packable ? (sk[q] << LOGH) | at : sk[q]; vals[at] = sv[q]; ++at; }
       int nsort = 2;
       while (nsort < filled) nsort <<= 1;
       for (int t = filled + gl; t < nsort; t += GROUP) keys[t] = kPadKey;
       group_sync<GROUP>();
-      bitonic_sort_lds<GROUP, H, double>(keys, vals, nsort, gl);
+      if (packable) bitonic_sort_lds<GROUP, H, double>(keys, nullptr, nsort, gl);
+      else bitonic_sort_lds<GROUP, H, double>(keys, vals, nsort, gl);
       if (live) {
         const int64_t out = c_rp[row];
         const int n = (int)(c_rp[row + 1] - out);
         for (int t = gl; t < n; t += GROUP) {
-          c_col[out + t] = keys[t];
-          c_val[out + t] = (T)vals[t];
+          const int kv = keys[t];
+          c_col[out + t] = packable ? kv >> LOGH : kv;
+          c_val[out + t] = (T)vals[packable ? kv & (H - 1) : t];
         }
       }
     }

@@ -330,12 +330,12 @@ int run_symbolic(spgemm_context* h, spgemm_plan_s* p, const spgemm_csr* A, const
       if (hist[2])
         hipLaunchKernelGGL((k_hash<64, 10, T, false>), dim3(grid_for(hist[2], 4, cap_small)), dim3(256), lds_hash_small, s,
                            p->perm_sym, p->ctl, 0, 2, p->ip, A->rowptr, A->colidx, (const T*)nullptr, B->rowptr, B->colidx,
-                           (const T*)nullptr, p->cnt, (const int64_t*)nullptr, (int32_t*)nullptr, (T*)nullptr);
+                           (const T*)nullptr, p->cnt, (const int64_t*)nullptr, (int32_t*)nullptr, (T*)nullptr, B->cols);
       if (hist[3])
         hipLaunchKernelGGL((k_hash<256, 12, T, false>), dim3(grid_for(hist[3], 1, (int64_t)h->num_cus * 8)), dim3(256),
                            lds_hash_large, s, p->perm_sym, p->ctl, 0, 3, p->ip, A->rowptr, A->colidx,
                            (const T*)nullptr, B->rowptr, B->colidx, (const T*)nullptr, p->cnt, (const int64_t*)nullptr,
-                           (int32_t*)nullptr, (T*)nullptr);
+                           (int32_t*)nullptr, (T*)nullptr, B->cols);
     }
     if (rows_dense > 0) {
       Timer t(h, SPGEMM_K_SYM_DENSE);
@@ -395,11 +395,11 @@ int run_numeric(spgemm_context* h, spgemm_plan_s* p, const spgemm_csr* A, const 
     if (hist[2])
       hipLaunchKernelGGL((k_hash<64, 8, T, true>), dim3(grid_for(hist[2], 4, cap_small)), dim3(256), lds_hash_small, s,
                          p->perm_num, p->ctl, 1, 2, p->ip, A->rowptr, A->colidx, a_val, B->rowptr, B->colidx, b_val, (int*)nullptr,
-                         c_rp, c_col, c_val);
+                         c_rp, c_col, c_val, B->cols);
     if (hist[3])
       hipLaunchKernelGGL((k_hash<256, 11, T, true>), dim3(grid_for(hist[3], 1, (int64_t)h->num_cus * 8)), dim3(256),
                          lds_hash_large, s, p->perm_num, p->ctl, 1, 3, p->ip, A->rowptr, A->colidx, a_val, B->rowptr,
-                         B->colidx, b_val, (int*)nullptr, c_rp, c_col, c_val);
+                         B->colidx, b_val, (int*)nullptr, c_rp, c_col, c_val, B->cols);
   }
   if (hist[4]) {
     Timer t(h, SPGEMM_K_NUM_STAGED);

@@ -59,6 +59,14 @@ def test_randomized_shapes_every_route(seed):
         ref = assert_matches_oracle(A, B, got, ref=ref, what=f"seed {seed} force={force} {m}x{k}x{B.cols}")
 
 
+def test_hash_retrieval_with_columns_too_wide_to_pack():
+    # beyond 2^20 (large class) and 2^23 (small class) columns the hash workspace sorts (column, sum)
+    # pairs instead of packed (column, slot) words
+    A = W.random_csr(500, 400, 8, 81)
+    run(A, W.random_csr(400, 3_000_000, 40, 82), HASH, what="hash, 3M columns")
+    run(A, W.random_csr(400, 9_000_000, 10, 83), HASH, what="hash, 9M columns")
+
+
 def test_stencil_small_grid():
     a, b = W.config2(g=12)
     st = run(a, b, what="stencil 12^3")

@@ -41,10 +41,12 @@ __global__ __launch_bounds__(256) void k_validate_b(int64_t rows, int64_t cols, 
   }
 }
 
-// One workgroup of 256 threads per 256 consecutive rows of A: the chunk's A entries are
-// read coalesced, each entry adds the length of its B row to its row's counter in LDS.
+// One workgroup of 1024 threads per 256 consecutive rows of A (a chunk of hub rows holds a large
+// share of all entries, so the chunk gets the widest workgroup): the chunk's A entries are read
+// coalesced, each entry adds the length of its B row to its row's counter in LDS.
 // Writes ip (saturated to int32), the symbolic bin, zero counts for rows without products.
-__global__ __launch_bounds__(256) void k_count_rows(int64_t m, int64_t nnz_a, int64_t b_rows,
+constexpr int kCountThreads = 1024;
+__global__ __launch_bounds__(kCountThreads) void k_count_rows(int64_t m, int64_t nnz_a, int64_t b_rows,
                                                     const int64_t* __restrict__ a_rp, const int32_t* __restrict__ a_col,
                                                     const int64_t* __restrict__ b_rp, int* __restrict__ ip_out,
                                                     unsigned char* __restrict__ bin_out, int* __restrict__ cnt_out,
@@ -59,8 +61,8 @@ __global__ __launch_bounds__(256) void k_count_rows(int64_t m, int64_t nnz_a, in
   const int nr = (int)((m - r0) < 256 ? (m - r0) : 256);
   if (tid < kNumBins) { hist[tid] = 0; hip[tid] = 0; }
   if (tid == 0) bad = 0;
-  for (int t = tid; t <= nr; t += 256) rp[t] = a_rp[r0 + t];
-  ipl[tid] = 0;
+  for (int t = tid; t <= nr; t += kCountThreads) rp[t] = a_rp[r0 + t];
+  if (tid < 256) ipl[tid] = 0;
   __syncthreads();
   if (tid < nr && rp[tid + 1] < rp[tid]) bad = 1;
   if (tid == 0) {
@@ -76,17 +78,17 @@ __global__ __launch_bounds__(256) void k_count_rows(int64_t m, int64_t nnz_a, in
   const long long lo = rp[0], hi = rp[nr];
   bool badcol = false;
   // four entries per thread and round, so that their (dependent) loads overlap
-  for (long long p0 = lo + tid; p0 < hi; p0 += 256 * 4) {
+  for (long long p0 = lo + tid; p0 < hi; p0 += kCountThreads * 4) {
     int k[4];
     long long len[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-      const long long p = p0 + u * 256;
+      const long long p = p0 + u * kCountThreads;
       k[u] = p < hi ? a_col[p] : -1;
     }
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-      const long long p = p0 + u * 256;
+      const long long p = p0 + u * kCountThreads;
       len[u] = 0;
       if (p < hi) {
         if (k[u] < 0 || k[u] >= b_rows) { badcol = true; continue; }
@@ -96,7 +98,7 @@ __global__ __launch_bounds__(256) void k_count_rows(int64_t m, int64_t nnz_a, in
     }
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-      const long long p = p0 + u * 256;
+      const long long p = p0 + u * kCountThreads;
       if (len[u] > 0) {
         // row of entry p: last t with rp[t] <= p
         int a = 0, b = nr;
@@ -123,11 +125,12 @@ __global__ __launch_bounds__(256) void k_count_rows(int64_t m, int64_t nnz_a, in
   // block total of ip
   unsigned long long s = mine;
   for (int d = 32; d > 0; d >>= 1) s += __shfl_xor(s, d, kWave);
-  __shared__ unsigned long long wsum[4];
+  __shared__ unsigned long long wsum[kCountThreads / kWave];
   if ((tid & 63) == 0) wsum[tid >> 6] = s;
   __syncthreads();
   if (tid == 0) {
-    const unsigned long long tot = wsum[0] + wsum[1] + wsum[2] + wsum[3];
+    unsigned long long tot = 0;
+    for (int w = 0; w < kCountThreads / kWave; ++w) tot += wsum[w];
     if (tot) atomicAdd(&ctl->ip_total, tot);
   }
   if (tid < kNumBins && hist[tid]) {

@@ -213,7 +213,7 @@ int run_setup(spgemm_context* h, spgemm_plan_s* p, const spgemm_csr* A, const sp
     hipLaunchKernelGGL(k_validate_b, dim3(grid_for(B->nnz > B->rows ? B->nnz : B->rows, 256 * 8, (int64_t)h->num_cus * 16)), dim3(256), 0, s,
                        B->rows, B->cols, B->nnz, B->rowptr, B->colidx, p->ctl);
     if (m > 0)
-      hipLaunchKernelGGL(k_count_rows, dim3((unsigned)ceil_div(m, 256)), dim3(256), 0, s, m, A->nnz, B->rows, A->rowptr, A->colidx,
+      hipLaunchKernelGGL(k_count_rows, dim3((unsigned)ceil_div(m, 256)), dim3(kCountThreads), 0, s, m, A->nnz, B->rows, A->rowptr, A->colidx,
                          B->rowptr, p->ip, p->bin, p->cnt, p->ctl, h->force);
   }
   {

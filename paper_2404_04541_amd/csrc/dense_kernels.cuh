@@ -81,20 +81,21 @@ struct RowScratch {
 };
 
 // Exclusive scans of two ints over the workgroup, with totals.  Contains barriers.
+// The 16 wave totals are scanned by every wave itself: lane w reads the total of wave w, a DPP row
+// scan adds them up, and the wave takes its own prefix and the grand total with readlane.
 __device__ __forceinline__ void block_excl_scan2(int a, int b, int& ea, int& eb, int& ta, int& tb, int* red) {
-  const int wave = threadIdx.x >> 6;
+  static_assert(kDenseWaves == 16, "one DPP row of wave totals");
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int ia = wave_incl_scan(a), ib = wave_incl_scan(b);
   __syncthreads();
   if (lane_id() == kWave - 1) { red[wave] = ia; red[kDenseWaves + wave] = ib; }
   __syncthreads();
-  int pa = 0, pb = 0;
-  ta = 0; tb = 0;
-#pragma unroll
-  for (int w = 0; w < kDenseWaves; ++w) {
-    const int va = red[w], vb = red[kDenseWaves + w];
-    if (w < wave) { pa += va; pb += vb; }
-    ta += va; tb += vb;
-  }
+  const int l = lane_id() & (kDenseWaves - 1);
+  const int sa = group_incl_scan<16>(red[l]), sb = group_incl_scan<16>(red[kDenseWaves + l]);
+  ta = __builtin_amdgcn_readlane(sa, kDenseWaves - 1);
+  tb = __builtin_amdgcn_readlane(sb, kDenseWaves - 1);
+  const int pa = wave ? __builtin_amdgcn_readlane(sa, wave - 1) : 0;
+  const int pb = wave ? __builtin_amdgcn_readlane(sb, wave - 1) : 0;
   ea = pa + ia - a;
   eb = pb + ib - b;
 }

@@ -275,7 +275,7 @@ __device__ __forceinline__ void plan_head(TilePlan* tp, int nb, bool count_only)
   const int c0 = l < nb ? tp->blk_cnt[l] : 0;
   const int c1 = l + 64 < nb ? tp->blk_cnt[l + 64] : 0;
   const int i0 = wave_incl_scan(c0);
-  const int t0 = __shfl(i0, 63, kWave);
+  const int t0 = __builtin_amdgcn_readlane(i0, 63);
   const int i1 = wave_incl_scan(c1);
   tp->cum[l] = i0 - c0;
   tp->cum[l + 64] = t0 + i1 - c1;
@@ -515,7 +515,7 @@ __global__ __launch_bounds__(kDenseThreads) void k_sym_dense(const int* __restri
             unsigned bits = flags[w];
             const int c = __popc(bits);
             const int incl = wave_incl_scan(c);
-            const int tot = __shfl(incl, kWave - 1, kWave);
+            const int tot = __builtin_amdgcn_readlane(incl, kWave - 1);
             if (tot == 0) continue;
             int excl = incl - c;
             const int cbase = lo + w * 32;
@@ -982,7 +982,7 @@ __device__ __forceinline__ void num_dense_run(const RunRec rr, NumScratch<T>* ns
         const int c = __popc(bits);
         const int incl = wave_incl_scan(c);
         int excl = running + incl - c;
-        running += __shfl(incl, kWave - 1, kWave);
+        running += __builtin_amdgcn_readlane(incl, kWave - 1);
         if (w < nw) fc[w].y = (unsigned)excl;
         const int cbase = t_lo + w * 32;
         while (bits) {   // columns are decoded from the flag words ("boolean indexing")

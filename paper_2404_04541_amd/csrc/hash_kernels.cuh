@@ -32,7 +32,7 @@ template <int GROUP>
 __device__ __forceinline__ int group_excl_scan(int v, int& total, int* part) {
   const int incl = wave_incl_scan(v);
   if constexpr (GROUP <= kWave) {
-    total = __shfl(incl, kWave - 1, kWave);
+    total = __builtin_amdgcn_readlane(incl, kWave - 1);
     return incl - v;
   } else {
     constexpr int kW = GROUP / kWave;

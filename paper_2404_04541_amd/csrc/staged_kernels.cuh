@@ -230,7 +230,7 @@ __global__ __launch_bounds__(kDenseThreads) void k_num_staged(const int* __restr
         const int c = __popc(bits);
         const int incl = wave_incl_scan(c);
         int excl = running + incl - c;
-        running += __shfl(incl, kWave - 1, kWave);
+        running += __builtin_amdgcn_readlane(incl, kWave - 1);
         fc[wi].y = (unsigned)excl;
         const int cbase = w_lo + wi * 32;
         while (bits) {

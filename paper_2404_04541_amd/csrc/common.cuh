@@ -45,7 +45,32 @@ struct Control {
   unsigned long long bin_nnz[kNumBins];     // output entries per numeric bin
   long long nnz_c;
   long long scan_blocks;
+#ifdef SPG_PHASE_CLOCKS
+  unsigned long long clk[2][32];   // [0] dense symbolic, [1] dense numeric: shader clocks per phase, summed over workgroups
+#endif
 };
+
+// Optional phase clocks of the two dense kernels (a build with -DSPG_PHASE_CLOCKS; the product is
+// built without): thread 0 of a workgroup reads the shader clock at phase boundaries and adds the
+// differences up in LDS; at the end of the kernel the sums go to the control block.  Nothing is
+// skipped or reordered, the marks only add a scalar clock read and one LDS update each.
+#ifdef SPG_PHASE_CLOCKS
+constexpr int kClkSlots = 32;
+struct ClkLds { unsigned long long t, acc[kClkSlots]; };
+__device__ __forceinline__ void clk_begin(ClkLds* c) {
+  if (threadIdx.x == 0) { for (int i = 0; i < kClkSlots; ++i) c->acc[i] = 0; c->t = __builtin_readcyclecounter(); }
+}
+__device__ __forceinline__ void clk_mark(ClkLds* c, int slot) {
+  if (threadIdx.x == 0) { const unsigned long long n = __builtin_readcyclecounter(); c->acc[slot] += n - c->t; c->t = n; }
+}
+__device__ __forceinline__ void clk_add(ClkLds* c, int slot, unsigned long long v) { if (threadIdx.x == 0) c->acc[slot] += v; }
+__device__ __forceinline__ void clk_flush(ClkLds* c, unsigned long long* out) {
+  if (threadIdx.x == 0) for (int i = 0; i < kClkSlots; ++i) if (c->acc[i]) atomicAdd(&out[i], c->acc[i]);
+}
+#define SPG_CLK(...) __VA_ARGS__
+#else
+#define SPG_CLK(...)
+#endif
 
 __device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
 

@@ -78,6 +78,7 @@ struct RowScratch {
   int red[2 * kDenseWaves];
   int s_row;
   int pad;
+  SPG_CLK(ClkLds clk;)
 };
 
 // Exclusive scans of two ints over the workgroup, with totals.  Contains barriers.
@@ -133,6 +134,7 @@ __device__ __forceinline__ void stream_columns(int64_t a0, int d, const int32_t*
     rs->spre[tid] = es;
     if (tid == 0) { rs->cpre[kDenseThreads] = tc; rs->spre[kDenseThreads] = ts; }
     __syncthreads();
+    SPG_CLK(clk_mark(&rs->clk, 2); clk_add(&rs->clk, 18, 1); clk_add(&rs->clk, 19, (unsigned long long)tc);)
     if (tc > 0) {
       const int per = (tc + kDenseWaves - 1) / kDenseWaves;
       int c = wave * per;
@@ -166,6 +168,7 @@ __device__ __forceinline__ void stream_columns(int64_t a0, int d, const int32_t*
         }
       }
     }
+    SPG_CLK(clk_mark(&rs->clk, 3);)
     for (int t = tid; t < ts; t += kDenseThreads) {
       int lo = 0, hi = kDenseThreads;
       while (hi - lo > 1) {
@@ -175,6 +178,7 @@ __device__ __forceinline__ void stream_columns(int64_t a0, int d, const int32_t*
       f(b_col[rs->start[lo] + (t - rs->spre[lo])]);
     }
     __syncthreads();
+    SPG_CLK(clk_mark(&rs->clk, 4);)
   }
 }
 
@@ -367,12 +371,14 @@ __global__ __launch_bounds__(kDenseThreads) void k_sym_dense(const int* __restri
   const unsigned row_lo = ctl->offset[0][4], row_hi = ctl->offset[0][7];   // the dense bins, heaviest class last
   const unsigned tile_cap = ctl->tile_cap, run_cap = ctl->run_cap;
   const unsigned long long list_cap = ctl->list_cap;
+  SPG_CLK(clk_begin(&rs->clk);)
   int row = next_dense_row(perm, ctl, &rs->s_row);
   int next_row = -1;   // (thread 0) the row after this one, fetched while this one is in the works
   while (row >= 0) {
     const int64_t a0 = a_rp[row];
     const int d = (int)(a_rp[row + 1] - a0);
     if (tid == 0) tp->row_out = 0;
+    SPG_CLK(clk_mark(&rs->clk, 0); clk_add(&rs->clk, 16, 1);)
     for (int64_t c0 = 0; c0 < n_cols; c0 += span) {
       const int64_t c1 = (c0 + span < n_cols) ? c0 + span : n_cols;
       const int words = (int)((c1 - c0 + 31) >> 5);
@@ -384,6 +390,7 @@ __global__ __launch_bounds__(kDenseThreads) void k_sym_dense(const int* __restri
       if (tid < kSpanBlocks) tp->blk_cnt[tid] = 0;
       if (tid == 0) { tp->span_out0 = tp->row_out; tp->list_base = -1; }
       __syncthreads();
+      SPG_CLK(clk_mark(&rs->clk, 1); clk_add(&rs->clk, 17, 1);)
       const int lo = (int)c0;
       const int64_t hi = c1;
       auto mark = [&](int c) {
@@ -408,6 +415,7 @@ __global__ __launch_bounds__(kDenseThreads) void k_sym_dense(const int* __restri
         if ((tid & 7) == 0) tp->blk_cnt[tid >> 3] = local;
       }
       __syncthreads();
+      SPG_CLK(clk_mark(&rs->clk, 5);)
       const bool count_only = ip[row] <= no_tiles_ip;
       const bool whole_row = n_cols <= span;
       const bool last_span = c1 >= n_cols;
@@ -417,6 +425,7 @@ __global__ __launch_bounds__(kDenseThreads) void k_sym_dense(const int* __restri
         if (!count_only) plan_tail(tp, nb, block0, direct_min);
       }
       __syncthreads();
+      SPG_CLK(clk_mark(&rs->clk, 6);)
       if (tid == 0) {
         // Everything this span needs from the plan's shared lists, and the next row, in one round trip:
         // room for the entries in the column list (without it the numeric kernel rebuilds the flags
@@ -454,6 +463,7 @@ __global__ __launch_bounds__(kDenseThreads) void k_sym_dense(const int* __restri
         if (last_span) next_row = nx < row_hi - row_lo ? perm[row_hi - 1 - nx] : -1;
       }
       __syncthreads();
+      SPG_CLK(clk_mark(&rs->clk, 7);)
       const long long lb = tp->list_base;
       const int nt = tp->ntiles;
       if (nt > 0 || tp->nruns > 0) {
@@ -540,6 +550,7 @@ __global__ __launch_bounds__(kDenseThreads) void k_sym_dense(const int* __restri
         }
       }
       __syncthreads();
+      SPG_CLK(clk_mark(&rs->clk, 8);)
     }
     if (tid == 0) {
       cnt[row] = tp->row_out;
@@ -548,6 +559,7 @@ __global__ __launch_bounds__(kDenseThreads) void k_sym_dense(const int* __restri
     __syncthreads();
     row = rs->s_row;
   }
+  SPG_CLK(clk_mark(&rs->clk, 9); clk_flush(&rs->clk, ctl->clk[0]);)
 }
 
 constexpr size_t kSymDenseLds = (size_t)kSymFlagWords * 4 + sizeof(RowScratch) + sizeof(TilePlan);
@@ -566,6 +578,7 @@ struct NumScratch {
   int red[2 * kDenseWaves];
   int s_run;
   int pad;
+  SPG_CLK(ClkLds clk;)
 };
 
 constexpr int kChunkUnroll = 8;
@@ -705,6 +718,7 @@ __device__ __forceinline__ void tile_pieces(NumScratch<T>* ns, long long s, int 
   }
   if (threadIdx.x == 0) ns->c_cpre[np] = nchunks;
   __syncthreads();
+  SPG_CLK(clk_add(&ns->clk, 20, (unsigned long long)nchunks); clk_add(&ns->clk, 21, (unsigned long long)np);)
 }
 
 template <typename T, bool CHECK>
@@ -747,6 +761,7 @@ __device__ __forceinline__ void num_dense_run(const RunRec rr, NumScratch<T>* ns
       }
     }
   }
+  SPG_CLK(clk_mark(&ns->clk, 1);)
   for (int t = 0; t < rr.count; ++t) {
     const TileRec tr = ns->rec[t];
     const bool direct = (tr.cnt & kDirectBit) != 0;
@@ -802,6 +817,7 @@ __device__ __forceinline__ void num_dense_run(const RunRec rr, NumScratch<T>* ns
     T my_av = T(0);
     if (nseg == 1) seg_piece(0, s, len, my_av);
     __syncthreads();   // the previous tile's output has left the tile area
+    SPG_CLK(clk_mark(&ns->clk, 2); clk_add(&ns->clk, 22, (unsigned long long)count);)
     if (searched) {
       // the tile's columns (from the plan's list) and their sums, by rank; a product finds the rank of
       // its column by bisection, so the tile may be as wide as the matrix
@@ -825,6 +841,7 @@ __device__ __forceinline__ void num_dense_run(const RunRec rr, NumScratch<T>* ns
           }
         }
       }
+      SPG_CLK(clk_mark(&ns->clk, 10); clk_add(&ns->clk, 19, 1);)
       int top = 1;   // largest power of two below count
       while (top * 2 < count) top *= 2;
       for (int sg = 0; sg < nseg; ++sg) {
@@ -855,7 +872,9 @@ __device__ __forceinline__ void num_dense_run(const RunRec rr, NumScratch<T>* ns
         if (nseg > 1) __syncthreads();
       }
       __syncthreads();
+      SPG_CLK(clk_mark(&ns->clk, 11);)
       for (int r = tid; r < count; r += kDenseThreads) stream_store(&c_val[out + r], (T)acc[r]);
+      SPG_CLK(clk_mark(&ns->clk, 12);)
     } else if (direct) {
       double* acc = reinterpret_cast<double*>(tile);                      // kBlkCols sums, indexed by column
       int* stage = reinterpret_cast<int*>(tile + (size_t)kBlkCols * 8);   // kBlkCols columns, by rank
@@ -866,11 +885,13 @@ __device__ __forceinline__ void num_dense_run(const RunRec rr, NumScratch<T>* ns
       }
       // which columns exist: the flag words are in the plan's list, or are rebuilt by the pass
       if (tid < kBlkCols / 32) flags[tid] = have_list ? (unsigned)col_list[list_at + tr.out + tid] : 0u;
+      SPG_CLK(clk_add(&ns->clk, 18, 1);)
       for (int sg = 0; sg < nseg; ++sg) {
         T av = my_av;
         if (nseg > 1) seg_piece(sg, s, len, av);
         int np, nchunks;
         tile_pieces(ns, s, len, av, np, nchunks);
+        SPG_CLK(clk_mark(&ns->clk, 7);)
         chunk_pass<true, T>(np, nchunks, ns, b_col, b_val, [&](int c, T a, T b) {
           if (!CHECK || (c >= t_lo && (int64_t)c < t_hi)) {
             const int rel = c - t_lo;
@@ -881,6 +902,7 @@ __device__ __forceinline__ void num_dense_run(const RunRec rr, NumScratch<T>* ns
         if (nseg > 1) __syncthreads();
       }
       __syncthreads();
+      SPG_CLK(clk_mark(&ns->clk, 8);)
       // compress: thread t owns columns [8 t, 8 t + 8)
       const unsigned byte = (flags[tid >> 2] >> ((tid & 3) * 8)) & 255u;
       double v[8];
@@ -905,6 +927,7 @@ __device__ __forceinline__ void num_dense_run(const RunRec rr, NumScratch<T>* ns
         stream_store(&c_val[out + r], (T)acc[r]);
         stream_store(&c_col[out + r], stage[r]);
       }
+      SPG_CLK(clk_mark(&ns->clk, 9);)
     } else {
       const int nw = (tr.b1 - tr.b0) * (kBlkCols / 32);                   // 32-bit flag words
       uint2* fc = reinterpret_cast<uint2*>(tile);                         // per word: .x flag bits, .y rank of its first column
@@ -928,6 +951,7 @@ __device__ __forceinline__ void num_dense_run(const RunRec rr, NumScratch<T>* ns
         // come from that list, and the list is this tile's run of C's column indices
         for (int r = tid; r < count; r += kDenseThreads) acc[r] = 0.0;
         if (nseg == 1) tile_pieces(ns, s, len, my_av, np, nchunks); else __syncthreads();
+        SPG_CLK(clk_mark(&ns->clk, 3); clk_add(&ns->clk, 17, 1);)
         for (int j0 = 0; j0 < count; j0 += kListBatch * kDenseThreads) {
           if (j0 > 0) fetch_list(j0);
 #pragma unroll
@@ -945,6 +969,7 @@ __device__ __forceinline__ void num_dense_run(const RunRec rr, NumScratch<T>* ns
           }
         }
         __syncthreads();
+        SPG_CLK(clk_mark(&ns->clk, 4);)
       } else {
       // pass 1: which columns of the tile exist in the row
       for (int sg = 0; sg < nseg; ++sg) {
@@ -993,6 +1018,7 @@ __device__ __forceinline__ void num_dense_run(const RunRec rr, NumScratch<T>* ns
       }
       for (int r = tid; r < count; r += kDenseThreads) acc[r] = 0.0;
       __syncthreads();
+      SPG_CLK(clk_mark(&ns->clk, 13);)
       }
       // pass 2: accumulate a_ik * b_kj at the rank of column j
       for (int sg = 0; sg < nseg; ++sg) {
@@ -1013,12 +1039,10 @@ __device__ __forceinline__ void num_dense_run(const RunRec rr, NumScratch<T>* ns
         if (nseg > 1) __syncthreads();
       }
       __syncthreads();
+      SPG_CLK(clk_mark(&ns->clk, 5);)
       // compress: sums and columns are already in ascending column order
-      if (have_list) {
-        for (int r = tid; r < count; r += kDenseThreads) stream_store(&c_val[out + r], (T)acc[r]);
-      } else {
-        for (int r = tid; r < count; r += kDenseThreads) stream_store(&c_val[out + r], (T)acc[r]);
-      }
+      for (int r = tid; r < count; r += kDenseThreads) stream_store(&c_val[out + r], (T)acc[r]);
+      SPG_CLK(clk_mark(&ns->clk, 6);)
     }
   }
 }
@@ -1045,6 +1069,7 @@ __global__ __launch_bounds__(kDenseThreads) void k_num_dense(Control* ctl, const
   unsigned drawn = 0;
   RunRec coming{};
   bool have_coming = false;
+  SPG_CLK(clk_begin(&ns->clk);)
   if (tid == 0) {
     const unsigned first = atomicAdd(&ctl->work[1], 1u);
     drawn = atomicAdd(&ctl->work[1], 1u);
@@ -1083,11 +1108,13 @@ __global__ __launch_bounds__(kDenseThreads) void k_num_dense(Control* ctl, const
     }
     if (cls < 5 || cls > 6) continue;   // the row's numeric class is not this kernel's
     __syncthreads();
+    SPG_CLK(clk_mark(&ns->clk, 0); clk_add(&ns->clk, 16, 1);)
     if (sorted)
       num_dense_run<T, false>(rr, ns, tile, true, a_col, a_val, b_rp, b_col, b_val, n_cols, bp, nb1, col_list, out_row, c_col, c_val, pre_k, pre_av);
     else
       num_dense_run<T, true>(rr, ns, tile, false, a_col, a_val, b_rp, b_col, b_val, n_cols, bp, nb1, col_list, out_row, c_col, c_val, pre_k, pre_av);
   }
+  SPG_CLK(clk_mark(&ns->clk, 14); clk_flush(&ns->clk, ctl->clk[1]);)
 }
 
 template <typename T>

@@ -4,6 +4,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <cstddef>
 #include <cstdio>
 #include <cstring>
 #include <new>
@@ -365,6 +366,7 @@ int run_symbolic(spgemm_context* h, spgemm_plan_s* p, const spgemm_csr* A, const
 
 __global__ void k_reset_numeric_work(Control* ctl) {
   if (threadIdx.x == 0) { ctl->work[1] = 0; ctl->work[2] = 0; }
+  SPG_CLK(if (threadIdx.x < kClkSlots) ctl->clk[1][threadIdx.x] = 0;)
 }
 
 template <typename T>
@@ -604,6 +606,19 @@ int spgemm_numeric(spgemm_handle h, spgemm_plan p, const spgemm_csr* A, const sp
   p->numeric_pending = h->timing != 0;
   return SPGEMM_OK;
 }
+
+#ifdef SPG_PHASE_CLOCKS
+// Profiling builds only: shader clocks per phase of the dense kernels (2 x 32 values, host), summed
+// over workgroups, of the plan's last symbolic and numeric runs.  Waits for the stream.
+int spgemm_debug_phase_clocks(spgemm_plan p, unsigned long long* out) {
+  if (!p || !out) return SPGEMM_INVALID_ARG;
+  spgemm_context* h = p->h;
+  HIP_TRY(h, hipStreamSynchronize(h->stream));
+  HIP_TRY(h, hipMemcpy(out, reinterpret_cast<unsigned char*>(p->ctl) + offsetof(Control, clk), sizeof(unsigned long long) * 2 * kClkSlots,
+                       hipMemcpyDeviceToHost));
+  return SPGEMM_OK;
+}
+#endif
 
 int spgemm_free_device(spgemm_handle h, void* ptr) {
   if (!h) return SPGEMM_INVALID_ARG;

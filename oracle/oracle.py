@@ -110,23 +110,60 @@ def spgemm(A, B, threads: int = 0) -> OracleResult:
     return spgemm_rows(A.rowptr, A.colidx, A.values, B.rowptr, B.colidx, B.values, threads=threads)
 
 
+def _mode_axes(mode: int):
+    """Unfolding over `mode` (1, 2 or 3): the two kept modes form the row (earlier mode major), the
+    unfolded mode is the column.  Returns the positions (a, b, c) in (i, j, k) of row-major, row-minor, column."""
+    if mode not in (1, 2, 3):
+        raise ValueError("mode must be 1, 2 or 3")
+    return {1: (1, 2, 0), 2: (0, 2, 1), 3: (0, 1, 2)}[mode]
+
+
+def unfold(shape, mode, xi, xj, xk, xval):
+    """Mode-`mode` unfolding of a coordinate tensor X(i,j,k) (the index folding of the paper's section 7.4):
+    the two other coordinates fold into the row (mode 3: i*J + j; mode 2: i*K + k; mode 1: j*K + k), the
+    coordinate of `mode` is the column; entries ordered by (row, column), repeated coordinates kept as
+    separate entries in their order of appearance.  Returns (rowptr int64, colidx int32, values)."""
+    dims = tuple(int(v) for v in shape)
+    x = [np.asarray(xi, dtype=np.int64), np.asarray(xj, dtype=np.int64), np.asarray(xk, dtype=np.int64)]
+    for c, d in zip(x, dims):
+        if c.size and (c.min() < 0 or c.max() >= d):
+            raise ValueError("coordinate out of range")
+    a, b, c = _mode_axes(mode)
+    row = x[a] * dims[b] + x[b]
+    order = np.lexsort((np.arange(row.size), x[c], row))   # by row, then column, then input position
+    nrows = dims[a] * dims[b]
+    rowptr = np.zeros(nrows + 1, dtype=np.int64)
+    np.cumsum(np.bincount(row, minlength=nrows), out=rowptr[1:])
+    return rowptr, x[c][order].astype(np.int32), np.asarray(xval)[order]
+
+
+def spttm(shape, mode, xi, xj, xk, xval, M, threads: int = 0) -> OracleResult:
+    """Tensor times matrix over `mode`: the coordinate of that mode is replaced by l with
+    Y(..l..) = sum_x X(..x..) M(x,l), computed as the row-wise product of the mode unfolding with M.
+    Row r of the result is the same fold of the two kept coordinates as in unfold()."""
+    rowptr, colidx, values = unfold(shape, mode, xi, xj, xk, xval)
+    return spgemm_rows(rowptr, colidx, values, M.rowptr, M.colidx, M.values, threads=threads)
+
+
+def fold(shape, mode, rowptr, colidx):
+    """Coordinates (i, j, k) of the entries of a matrix that is the mode-`mode` unfolding of a tensor of
+    the given shape (after a contraction, shape[mode-1] is the matrix's column count)."""
+    dims = tuple(int(v) for v in shape)
+    a, b, c = _mode_axes(mode)
+    rowptr = np.asarray(rowptr, dtype=np.int64)
+    rows = np.repeat(np.arange(rowptr.size - 1, dtype=np.int64), np.diff(rowptr))
+    out = [None, None, None]
+    out[a] = (rows // dims[b]).astype(np.int32)
+    out[b] = (rows % dims[b]).astype(np.int32)
+    out[c] = np.asarray(colidx, dtype=np.int32).copy()
+    return tuple(out)
+
+
 def unfold_mode3(shape, xi, xj, xk, xval):
-    """Mode-3 unfolding of a coordinate tensor X(i,j,k) (the index folding of the paper's section 7.4):
-    row i*J + j, column k, entries ordered by (row, column), repeated coordinates kept as separate
-    entries in their order of appearance.  Returns (rowptr int64, colidx int32, values)."""
-    I, J, K = (int(v) for v in shape)
-    xi = np.asarray(xi, dtype=np.int64); xj = np.asarray(xj, dtype=np.int64); xk = np.asarray(xk, dtype=np.int64)
-    if xi.size and (xi.min() < 0 or xi.max() >= I or xj.min() < 0 or xj.max() >= J or xk.min() < 0 or xk.max() >= K):
-        raise ValueError("coordinate out of range")
-    row = xi * J + xj
-    order = np.lexsort((np.arange(row.size), xk, row))   # by row, then column, then input position
-    rowptr = np.zeros(I * J + 1, dtype=np.int64)
-    np.cumsum(np.bincount(row, minlength=I * J), out=rowptr[1:])
-    return rowptr, xk[order].astype(np.int32), np.asarray(xval)[order]
+    """unfold() over the third mode: row i*J + j, column k."""
+    return unfold(shape, 3, xi, xj, xk, xval)
 
 
 def spttm_mode3(shape, xi, xj, xk, xval, M, threads: int = 0) -> OracleResult:
-    """Y(i,j,l) = sum_k X(i,j,k) M(k,l) as the row-wise product of the mode-3 unfolding with M;
-    row i*J + j of the result holds Y(i,j,:)."""
-    rowptr, colidx, values = unfold_mode3(shape, xi, xj, xk, xval)
-    return spgemm_rows(rowptr, colidx, values, M.rowptr, M.colidx, M.values, threads=threads)
+    """spttm() over the third mode: row i*J + j of the result holds Y(i,j,:)."""
+    return spttm(shape, 3, xi, xj, xk, xval, M, threads=threads)

@@ -186,27 +186,45 @@ int spgemm_get_stats(spgemm_plan plan, spgemm_stats* out);
 /* Text of the last error on this handle (never null; valid until the next call). */
 const char* spgemm_last_error(spgemm_handle h);
 
-/* ---- sparse tensor times sparse matrix over the tensor's third mode ------------------------
- * Y(i,j,l) = sum_k X(i,j,k) M(k,l), computed on the row-wise path through the mode-3 unfolding
- * of X (the index folding that section 7.4 of the paper describes for its comparison system):
- * row i*J + j, column k.  X is given as device coordinate arrays xi, xj, xk (int32) and xval
- * (nnz each, any order, borrowed); a coordinate that occurs several times contributes several
- * products.  I*J and K must be below 2^31 - 1, nnz below 2^32 - 1.
- * Output matrices are device CSR whose buffers come from the handle's allocator (release with
- * its free or spgemm_free_device).  All three calls synchronise the handle's stream except
- * sptensor_fold_mode3, which only enqueues.
+/* ---- sparse tensor times sparse matrix through mode unfolding ------------------------------
+ * Y = X x_mode M for a 3-tensor X(i,j,k) given as device coordinate arrays xi, xj, xk (int32) and
+ * xval (nnz each, any order, borrowed): the coordinate of `mode` (1, 2 or 3) is contracted with the
+ * rows of M and replaced by M's column l, e.g. mode 3: Y(i,j,l) = sum_k X(i,j,k) M(k,l).  It is
+ * computed on the row-wise path through the unfolding of X over that mode (the index folding that
+ * section 7.4 of the paper describes for its comparison system; the paper's own SpTTM of section 7.4
+ * contracts one mode of a sparse tensor with a matrix into a sparse result, which is this operation):
+ * the two kept coordinates fold into the row, the earlier mode major (mode 3: i*J + j, mode 2:
+ * i*K + k, mode 1: j*K + k), the contracted coordinate is the column.  A coordinate that occurs
+ * several times contributes several products.  The folded row extent and the extent of the contracted
+ * mode must be below 2^31 - 1, nnz below 2^32 - 1.
+ * Output matrices are device CSR whose buffers come from the handle's allocator (release with its
+ * free or spgemm_free_device).  All calls synchronise the handle's stream except the fold calls,
+ * which only enqueue.
  * SPGEMM_INVALID_INPUT: a coordinate outside [0,I) x [0,J) x [0,K). */
 
-/* The unfolding itself: out = (I*J) x K CSR, columns ascending inside each row. */
+/* The unfolding itself: out = (product of the two kept extents) x (extent of `mode`) CSR, columns
+ * ascending inside each row, repeated coordinates kept as separate entries in input order. */
+int sptensor_unfold(spgemm_handle h, int mode, int64_t I, int64_t J, int64_t K, int64_t nnz, const int32_t* xi,
+                    const int32_t* xj, const int32_t* xk, const void* xval, int32_t dtype, spgemm_csr* out);
+
+/* Y = X x_mode M as the unfolded CSR matrix (rows as in sptensor_unfold, M->cols columns).
+ * SPGEMM_DIM_MISMATCH: M->rows differs from the extent of `mode`. */
+int spttm(spgemm_handle h, int mode, int64_t I, int64_t J, int64_t K, int64_t nnz, const int32_t* xi, const int32_t* xj,
+          const int32_t* xk, const void* xval, int32_t dtype, const spgemm_csr* M, spgemm_csr* Y);
+
+/* Folding back to a coordinate tensor: Y is the unfolding over `mode` of a tensor of extents I x J x K
+ * (so Y->rows is the product of the two kept extents and Y->cols the extent of `mode`); entry p of Y
+ * gets its three coordinates in yi[p], yj[p], yk[p] (device, Y->nnz each, caller-owned, written).
+ * The values of the coordinate tensor are Y->values as they are. */
+int sptensor_fold(spgemm_handle h, int mode, int64_t I, int64_t J, int64_t K, const spgemm_csr* Y, int32_t* yi, int32_t* yj,
+                  int32_t* yk);
+
+/* The same three calls for the third mode (row i*J + j, column k). */
 int sptensor_unfold_mode3(spgemm_handle h, int64_t I, int64_t J, int64_t K, int64_t nnz, const int32_t* xi,
                           const int32_t* xj, const int32_t* xk, const void* xval, int32_t dtype, spgemm_csr* out);
-
-/* Y = X x_3 M as the unfolded (I*J) x M.cols CSR matrix: row i*J + j holds Y(i,j,:). */
 int spttm_mode3(spgemm_handle h, int64_t I, int64_t J, int64_t K, int64_t nnz, const int32_t* xi, const int32_t* xj,
                 const int32_t* xk, const void* xval, int32_t dtype, const spgemm_csr* M, spgemm_csr* Y);
-
-/* Coordinates of the entries of an unfolded result: yi[p], yj[p] (device, Y->nnz each, caller-owned)
- * for entry p of Y; its third coordinate is Y->colidx[p]. */
+/* yi[p], yj[p] for entry p of Y; its third coordinate is Y->colidx[p]. */
 int sptensor_fold_mode3(spgemm_handle h, int64_t J, const spgemm_csr* Y, int32_t* yi, int32_t* yj);
 
 /* Library version: major*10000 + minor*100 + patch. */

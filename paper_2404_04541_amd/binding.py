@@ -28,7 +28,7 @@ STATUS_NAMES = {0: "OK", -1: "INVALID_ARG", -2: "DIM_MISMATCH", -3: "DTYPE_MISMA
 
 EXPORTED = ("spgemm_create", "spgemm_destroy", "spgemm_set_option", "spgemm_symbolic", "spgemm_numeric", "spgemm",
             "spgemm_free_device", "spgemm_plan_destroy", "spgemm_get_stats", "spgemm_last_error", "spgemm_version",
-            "sptensor_unfold_mode3", "spttm_mode3", "sptensor_fold_mode3")
+            "sptensor_unfold_mode3", "spttm_mode3", "sptensor_fold_mode3", "sptensor_unfold", "spttm", "sptensor_fold")
 
 
 class SpgemmError(RuntimeError):
@@ -84,6 +84,10 @@ def load_library():
     lib.sptensor_unfold_mode3.argtypes = tensor_args + [P(CsrStruct)]
     lib.spttm_mode3.argtypes = tensor_args + [P(CsrStruct), P(CsrStruct)]
     lib.sptensor_fold_mode3.argtypes = [C.c_void_p, C.c_int64, P(CsrStruct), C.c_void_p, C.c_void_p]
+    mode_args = [C.c_void_p, C.c_int] + tensor_args[1:]
+    lib.sptensor_unfold.argtypes = mode_args + [P(CsrStruct)]
+    lib.spttm.argtypes = mode_args + [P(CsrStruct), P(CsrStruct)]
+    lib.sptensor_fold.argtypes = [C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_int64, P(CsrStruct), C.c_void_p, C.c_void_p, C.c_void_p]
     lib.spgemm_last_error.argtypes = [C.c_void_p]
     lib.spgemm_last_error.restype = C.c_char_p
     for name in EXPORTED:
@@ -301,3 +305,32 @@ def sptensor_fold_mode3(handle: Handle, J: int, Y: DeviceCSR):
     handle._check(handle.lib.sptensor_fold_mode3(handle.ptr, int(J), C.byref(sy), yi.data_ptr() if Y.nnz else None,
                                                  yj.data_ptr() if Y.nnz else None))
     return yi, yj
+
+
+def _mode_args(handle, mode, shape, xi, xj, xk, xval):
+    a = _tensor_args(handle, shape, xi, xj, xk, xval)
+    return [a[0], int(mode)] + a[1:]
+
+
+def sptensor_unfold(handle: Handle, mode: int, shape, xi, xj, xk, xval) -> DeviceCSR:
+    """Unfolding of a coordinate tensor over `mode` (1, 2 or 3): the two kept coordinates fold into the row."""
+    sc = CsrStruct()
+    handle._check(handle.lib.sptensor_unfold(*_mode_args(handle, mode, shape, xi, xj, xk, xval), C.byref(sc)))
+    return _adopt_csr(handle, sc, xval.dtype, xval.device)
+
+
+def spttm(handle: Handle, mode: int, shape, xi, xj, xk, xval, M: DeviceCSR) -> DeviceCSR:
+    """Y = X x_mode M as the unfolded CSR matrix."""
+    sm, sc = M.struct(), CsrStruct()
+    handle._check(handle.lib.spttm(*_mode_args(handle, mode, shape, xi, xj, xk, xval), C.byref(sm), C.byref(sc)))
+    return _adopt_csr(handle, sc, xval.dtype, xval.device)
+
+
+def sptensor_fold(handle: Handle, mode: int, shape, Y: DeviceCSR):
+    """-> (yi, yj, yk) int32 device tensors: the coordinates of every entry of Y, the unfolding over `mode`
+    of a tensor of extents `shape`."""
+    out = [torch.empty(Y.nnz, dtype=torch.int32, device=Y.rowptr.device) for _ in range(3)]
+    sy = Y.struct()
+    I, J, K = (int(v) for v in shape)
+    handle._check(handle.lib.sptensor_fold(handle.ptr, int(mode), I, J, K, C.byref(sy), *[t.data_ptr() if Y.nnz else None for t in out]))
+    return tuple(out)

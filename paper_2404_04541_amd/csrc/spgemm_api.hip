@@ -667,53 +667,82 @@ int spgemm(spgemm_handle h, const spgemm_csr* A, const spgemm_csr* B, spgemm_csr
 }
 
 
-int sptensor_unfold_mode3(spgemm_handle h, int64_t I, int64_t J, int64_t K, int64_t nnz, const int32_t* xi, const int32_t* xj,
-                          const int32_t* xk, const void* xval, int32_t dtype, spgemm_csr* out) {
-  if (!h) return SPGEMM_INVALID_ARG;
-  if (!out) return fail(h, SPGEMM_INVALID_ARG, "out is null");
+// ---- sparse tensor entry points ------------------------------------------------------------
+
+namespace {
+
+// The unfolding over `mode`: which coordinate arrays and extents play row-major, row-minor, column.
+struct ModeView {
+  const int32_t *xa, *xb, *xc;
+  int64_t A, B, C;
+};
+
+bool mode_view(int mode, int64_t I, int64_t J, int64_t K, const int32_t* xi, const int32_t* xj, const int32_t* xk, ModeView* v) {
+  switch (mode) {
+    case 1: *v = ModeView{xj, xk, xi, J, K, I}; return true;
+    case 2: *v = ModeView{xi, xk, xj, I, K, J}; return true;
+    case 3: *v = ModeView{xi, xj, xk, I, J, K}; return true;
+    default: return false;
+  }
+}
+
+int check_tensor(spgemm_context* h, int mode, int64_t I, int64_t J, int64_t K, int64_t nnz, const int32_t* xi, const int32_t* xj,
+                 const int32_t* xk, const void* xval, int32_t dtype, ModeView* v) {
+  if (!mode_view(mode, I, J, K, xi, xj, xk, v)) return fail(h, SPGEMM_INVALID_ARG, "mode must be 1, 2 or 3");
   if (I < 0 || J < 0 || K < 0 || nnz < 0) return fail(h, SPGEMM_INVALID_ARG, "negative size");
   if (dtype != SPGEMM_F32 && dtype != SPGEMM_F64) return fail(h, SPGEMM_INVALID_ARG, "unknown dtype");
   if (nnz > 0 && (!xi || !xj || !xk || !xval)) return fail(h, SPGEMM_INVALID_ARG, "coordinate or value array null with nnz > 0");
-  if (K >= 0x7fffffffLL || (J > 0 && I > 0x7ffffffeLL / J) || nnz >= 0xffffffffLL)
-    return fail(h, SPGEMM_UNSUPPORTED, "I*J and K must be below 2^31 - 1, nnz below 2^32 - 1");
-  std::memset(out, 0, sizeof(*out));
-  int rc = ensure_device(h);
-  if (rc) return rc;
-  hipStream_t s = h->stream;
-  const int64_t rows = I * J;
-  const size_t vsz = dtype == SPGEMM_F32 ? 4 : 8;
-  int64_t* rp = static_cast<int64_t*>(dev_alloc(h, (size_t)(rows + 1) * 8));
-  int32_t* col = nnz ? static_cast<int32_t*>(dev_alloc(h, (size_t)nnz * 4)) : nullptr;
-  void* val = nnz ? dev_alloc(h, (size_t)nnz * vsz) : nullptr;
-  const int64_t ntiles = ceil_div(nnz > 0 ? nnz : 1, kSortTile);
+  if (v->C >= 0x7fffffffLL || (v->B > 0 && v->A > 0x7ffffffeLL / v->B) || nnz >= 0xffffffffLL)
+    return fail(h, SPGEMM_UNSUPPORTED, "the folded row extent and the column extent must be below 2^31 - 1, nnz below 2^32 - 1");
+  return SPGEMM_OK;
+}
+
+// Temporary memory of one unfolding: two key buffers, two index buffers, the tile histograms, one flag.
+struct UnfoldTmp {
+  size_t o_k0, o_k1, o_i0, o_i1, o_h, o_bad, bytes;
+  int64_t ntiles;
+};
+
+UnfoldTmp unfold_tmp_layout(int64_t nnz) {
+  UnfoldTmp t{};
+  t.ntiles = ceil_div(nnz > 0 ? nnz : 1, kSortTile);
   size_t off = 0;
-  const size_t o_k0 = off; off = align_up(off + (size_t)nnz * 8);
-  const size_t o_k1 = off; off = align_up(off + (size_t)nnz * 8);
-  const size_t o_i0 = off; off = align_up(off + (size_t)nnz * 4);
-  const size_t o_i1 = off; off = align_up(off + (size_t)nnz * 4);
-  const size_t o_h = off; off = align_up(off + (size_t)ntiles * 256 * 4);
-  const size_t o_bad = off; off = align_up(off + 4);
-  unsigned char* tmp = static_cast<unsigned char*>(dev_alloc(h, off));
-  auto release = [&](bool all) {
-    dev_free(h, tmp);
-    if (all) { dev_free(h, rp); dev_free(h, col); dev_free(h, val); }
-  };
-  if (!rp || !tmp || (nnz && (!col || !val))) { release(true); return fail(h, SPGEMM_ALLOC_FAILED, "allocation for the unfolding failed"); }
-  unsigned long long* keys[2] = {reinterpret_cast<unsigned long long*>(tmp + o_k0), reinterpret_cast<unsigned long long*>(tmp + o_k1)};
-  unsigned* idx[2] = {reinterpret_cast<unsigned*>(tmp + o_i0), reinterpret_cast<unsigned*>(tmp + o_i1)};
-  unsigned* hist = reinterpret_cast<unsigned*>(tmp + o_h);
-  int* bad = reinterpret_cast<int*>(tmp + o_bad);
+  t.o_k0 = off; off = align_up(off + (size_t)nnz * 8);
+  t.o_k1 = off; off = align_up(off + (size_t)nnz * 8);
+  t.o_i0 = off; off = align_up(off + (size_t)nnz * 4);
+  t.o_i1 = off; off = align_up(off + (size_t)nnz * 4);
+  t.o_h = off; off = align_up(off + (size_t)t.ntiles * 256 * 4);
+  t.o_bad = off; off = align_up(off + 4);
+  t.bytes = off;
+  return t;
+}
+
+__global__ void k_clear_int(int* p) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) *p = 0;
+}
+
+// Keys, stable radix sort, compress, row pointer; everything it touches is given by the caller.
+// Ends with one stream synchronisation (the out-of-range flag comes to the host).
+int unfold_run(spgemm_context* h, const ModeView& v, int64_t nnz, const void* xval, int32_t dtype, unsigned char* tmp, const UnfoldTmp& lay,
+               int64_t* rp, int32_t* col, void* val) {
+  hipStream_t s = h->stream;
+  const int64_t rows = v.A * v.B;
+  unsigned long long* keys[2] = {reinterpret_cast<unsigned long long*>(tmp + lay.o_k0), reinterpret_cast<unsigned long long*>(tmp + lay.o_k1)};
+  unsigned* idx[2] = {reinterpret_cast<unsigned*>(tmp + lay.o_i0), reinterpret_cast<unsigned*>(tmp + lay.o_i1)};
+  unsigned* hist = reinterpret_cast<unsigned*>(tmp + lay.o_h);
+  int* bad = reinterpret_cast<int*>(tmp + lay.o_bad);
   int host_bad = 0;
-  hipError_t e = hipMemsetAsync(bad, 0, 4, s);
+  const int64_t ntiles = lay.ntiles;
+  hipLaunchKernelGGL(k_clear_int, dim3(1), dim3(64), 0, s, bad);
   int cur = 0;
-  if (e == hipSuccess && nnz > 0) {
+  if (nnz > 0) {
     const unsigned g = grid_for(nnz, 256 * 4, (int64_t)h->num_cus * 32);
-    hipLaunchKernelGGL(k_tensor_keys, dim3(g), dim3(256), 0, s, nnz, I, J, K, xi, xj, xk, keys[0], idx[0], bad);
+    hipLaunchKernelGGL(k_tensor_keys, dim3(g), dim3(256), 0, s, nnz, v.A, v.B, v.C, v.xa, v.xb, v.xc, keys[0], idx[0], bad);
     auto bits_of = [](int64_t n) { int b = 0; while (n > 1 && (1LL << b) < n) ++b; return b; };   // bits that hold 0 .. n-1
-    const int bits_k = bits_of(K), bits_r = bits_of(rows);
+    const int bits_c = bits_of(v.C), bits_r = bits_of(rows);
     const unsigned gt = (unsigned)ceil_div(ntiles, kSortWgWaves);
     for (int part = 0; part < 2; ++part) {
-      const int base = part == 0 ? 0 : 32, nbits = part == 0 ? bits_k : bits_r;
+      const int base = part == 0 ? 0 : 32, nbits = part == 0 ? bits_c : bits_r;
       for (int shift = base; shift < base + nbits; shift += 8) {
         hipLaunchKernelGGL(k_radix_hist, dim3(gt), dim3(256), 0, s, nnz, ntiles, shift, keys[cur], hist);
         hipLaunchKernelGGL(k_scan_u32, dim3(1), dim3(1024), 0, s, ntiles * 256, hist);
@@ -729,36 +758,92 @@ int sptensor_unfold_mode3(spgemm_handle h, int64_t I, int64_t J, int64_t K, int6
       hipLaunchKernelGGL(k_tensor_compress<double>, dim3(g), dim3(256), 0, s, nnz, keys[cur], idx[cur], static_cast<const double*>(xval), col,
                          static_cast<double*>(val));
   }
-  if (e == hipSuccess) {
-    hipLaunchKernelGGL(k_tensor_rowptr, dim3(grid_for(rows + 1, 256, (int64_t)h->num_cus * 32)), dim3(256), 0, s, nnz, rows, keys[cur], rp);
-    e = hipGetLastError();
-  }
+  hipLaunchKernelGGL(k_tensor_rowptr, dim3(grid_for(rows + 1, 256, (int64_t)h->num_cus * 32)), dim3(256), 0, s, nnz, rows, keys[cur], rp);
+  hipError_t e = hipGetLastError();
   if (e == hipSuccess) e = hipMemcpyAsync(&host_bad, bad, 4, hipMemcpyDeviceToHost, s);
   if (e == hipSuccess) e = hipStreamSynchronize(s);
-  if (e != hipSuccess) { release(true); return fail(h, SPGEMM_HIP_ERROR, std::string("unfolding: ") + hipGetErrorString(e)); }
-  if (host_bad) { release(true); return fail(h, SPGEMM_INVALID_INPUT, "a tensor coordinate is outside its mode's range"); }
-  release(false);
-  out->rows = rows; out->cols = K; out->nnz = nnz; out->dtype = dtype;
+  if (e != hipSuccess) return fail(h, SPGEMM_HIP_ERROR, std::string("unfolding: ") + hipGetErrorString(e));
+  if (host_bad) return fail(h, SPGEMM_INVALID_INPUT, "a tensor coordinate is outside its mode's range");
+  return SPGEMM_OK;
+}
+
+}  // namespace
+
+int sptensor_unfold(spgemm_handle h, int mode, int64_t I, int64_t J, int64_t K, int64_t nnz, const int32_t* xi, const int32_t* xj,
+                    const int32_t* xk, const void* xval, int32_t dtype, spgemm_csr* out) {
+  if (!h) return SPGEMM_INVALID_ARG;
+  if (!out) return fail(h, SPGEMM_INVALID_ARG, "out is null");
+  ModeView v{};
+  int rc = check_tensor(h, mode, I, J, K, nnz, xi, xj, xk, xval, dtype, &v);
+  if (rc) return rc;
+  std::memset(out, 0, sizeof(*out));
+  if ((rc = ensure_device(h))) return rc;
+  const int64_t rows = v.A * v.B;
+  const size_t vsz = dtype == SPGEMM_F32 ? 4 : 8;
+  const UnfoldTmp lay = unfold_tmp_layout(nnz);
+  int64_t* rp = static_cast<int64_t*>(dev_alloc(h, (size_t)(rows + 1) * 8));
+  int32_t* col = nnz ? static_cast<int32_t*>(dev_alloc(h, (size_t)nnz * 4)) : nullptr;
+  void* val = nnz ? dev_alloc(h, (size_t)nnz * vsz) : nullptr;
+  unsigned char* tmp = static_cast<unsigned char*>(dev_alloc(h, lay.bytes));
+  if (!rp || !tmp || (nnz && (!col || !val))) rc = fail(h, SPGEMM_ALLOC_FAILED, "allocation for the unfolding failed");
+  if (rc == SPGEMM_OK) rc = unfold_run(h, v, nnz, xval, dtype, tmp, lay, rp, col, val);
+  dev_free(h, tmp);
+  if (rc != SPGEMM_OK) {
+    dev_free(h, rp); dev_free(h, col); dev_free(h, val);
+    return rc;
+  }
+  out->rows = rows; out->cols = v.C; out->nnz = nnz; out->dtype = dtype;
   out->rowptr = rp; out->colidx = col; out->values = val;
   return SPGEMM_OK;
 }
 
-int spttm_mode3(spgemm_handle h, int64_t I, int64_t J, int64_t K, int64_t nnz, const int32_t* xi, const int32_t* xj, const int32_t* xk,
-                const void* xval, int32_t dtype, const spgemm_csr* M, spgemm_csr* Y) {
+int sptensor_unfold_mode3(spgemm_handle h, int64_t I, int64_t J, int64_t K, int64_t nnz, const int32_t* xi, const int32_t* xj,
+                          const int32_t* xk, const void* xval, int32_t dtype, spgemm_csr* out) {
+  return sptensor_unfold(h, 3, I, J, K, nnz, xi, xj, xk, xval, dtype, out);
+}
+
+int spttm(spgemm_handle h, int mode, int64_t I, int64_t J, int64_t K, int64_t nnz, const int32_t* xi, const int32_t* xj, const int32_t* xk,
+          const void* xval, int32_t dtype, const spgemm_csr* M, spgemm_csr* Y) {
   if (!h) return SPGEMM_INVALID_ARG;
   if (!Y) return fail(h, SPGEMM_INVALID_ARG, "Y is null");
   int rc = check_csr(h, M, "M");
   if (rc) return rc;
-  if (M->rows != K) return fail(h, SPGEMM_DIM_MISMATCH, "M.rows differs from the tensor's third mode");
+  ModeView v{};
+  if (!mode_view(mode, I, J, K, xi, xj, xk, &v)) return fail(h, SPGEMM_INVALID_ARG, "mode must be 1, 2 or 3");
+  if (M->rows != v.C) return fail(h, SPGEMM_DIM_MISMATCH, "M.rows differs from the extent of the contracted mode");
   if (M->dtype != dtype) return fail(h, SPGEMM_DTYPE_MISMATCH, "tensor and matrix value types differ");
   spgemm_csr X{};
-  rc = sptensor_unfold_mode3(h, I, J, K, nnz, xi, xj, xk, xval, dtype, &X);
+  rc = sptensor_unfold(h, mode, I, J, K, nnz, xi, xj, xk, xval, dtype, &X);
   if (rc) return rc;
   rc = spgemm(h, &X, M, Y);
   dev_free(h, const_cast<int64_t*>(X.rowptr));
   dev_free(h, const_cast<int32_t*>(X.colidx));
   dev_free(h, const_cast<void*>(X.values));
   return rc;
+}
+
+int spttm_mode3(spgemm_handle h, int64_t I, int64_t J, int64_t K, int64_t nnz, const int32_t* xi, const int32_t* xj, const int32_t* xk,
+                const void* xval, int32_t dtype, const spgemm_csr* M, spgemm_csr* Y) {
+  return spttm(h, 3, I, J, K, nnz, xi, xj, xk, xval, dtype, M, Y);
+}
+
+int sptensor_fold(spgemm_handle h, int mode, int64_t I, int64_t J, int64_t K, const spgemm_csr* Y, int32_t* yi, int32_t* yj, int32_t* yk) {
+  if (!h) return SPGEMM_INVALID_ARG;
+  int rc = check_csr(h, Y, "Y");
+  if (rc) return rc;
+  ModeView v{};
+  if (!mode_view(mode, I, J, K, yi, yj, yk, &v)) return fail(h, SPGEMM_INVALID_ARG, "mode must be 1, 2 or 3");
+  if (I < 0 || J < 0 || K < 0) return fail(h, SPGEMM_INVALID_ARG, "negative size");
+  if (v.B <= 0 || Y->rows != v.A * v.B || Y->cols != v.C)
+    return fail(h, SPGEMM_DIM_MISMATCH, "Y is not the unfolding of a tensor of these extents over this mode");
+  if (Y->nnz > 0 && (!yi || !yj || !yk)) return fail(h, SPGEMM_INVALID_ARG, "coordinate arrays null with nnz > 0");
+  if (Y->nnz == 0 || Y->rows == 0) return SPGEMM_OK;
+  if ((rc = ensure_device(h))) return rc;
+  // (the view was built over the output arrays: xa / xb take the row's two coordinates, xc the column)
+  hipLaunchKernelGGL(k_tensor_fold, dim3(grid_for(Y->rows, 4, (int64_t)h->num_cus * 32)), dim3(256), 0, h->stream, Y->rows, v.B, Y->rowptr,
+                     Y->colidx, const_cast<int32_t*>(v.xa), const_cast<int32_t*>(v.xb), const_cast<int32_t*>(v.xc));
+  HIP_TRY(h, hipGetLastError());
+  return SPGEMM_OK;
 }
 
 int sptensor_fold_mode3(spgemm_handle h, int64_t J, const spgemm_csr* Y, int32_t* yi, int32_t* yj) {
@@ -769,7 +854,8 @@ int sptensor_fold_mode3(spgemm_handle h, int64_t J, const spgemm_csr* Y, int32_t
   if (Y->nnz > 0 && (!yi || !yj)) return fail(h, SPGEMM_INVALID_ARG, "coordinate arrays null with nnz > 0");
   if (Y->nnz == 0 || Y->rows == 0) return SPGEMM_OK;
   if ((rc = ensure_device(h))) return rc;
-  hipLaunchKernelGGL(k_tensor_fold, dim3(grid_for(Y->rows, 4, (int64_t)h->num_cus * 32)), dim3(256), 0, h->stream, Y->rows, J, Y->rowptr, yi, yj);
+  hipLaunchKernelGGL(k_tensor_fold, dim3(grid_for(Y->rows, 4, (int64_t)h->num_cus * 32)), dim3(256), 0, h->stream, Y->rows, J, Y->rowptr,
+                     (const int32_t*)nullptr, yi, yj, (int32_t*)nullptr);
   HIP_TRY(h, hipGetLastError());
   return SPGEMM_OK;
 }

@@ -129,15 +129,21 @@ __global__ __launch_bounds__(256) void k_tensor_rowptr(int64_t nnz, int64_t rows
   }
 }
 
-// Row i*J + j of the unfolded result back to coordinates: per entry of Y its (i, j); the column is l.
-__global__ __launch_bounds__(256) void k_tensor_fold(int64_t rows, int64_t J, const int64_t* __restrict__ rowptr, int32_t* __restrict__ yi,
-                                                     int32_t* __restrict__ yj) {
+// A row of an unfolded result back to coordinates: per entry the row's two folded coordinates
+// (row / B, row % B) and, when asked for, the column as the third.
+__global__ __launch_bounds__(256) void k_tensor_fold(int64_t rows, int64_t B, const int64_t* __restrict__ rowptr,
+                                                     const int32_t* __restrict__ colidx, int32_t* __restrict__ ya,
+                                                     int32_t* __restrict__ yb, int32_t* __restrict__ yc) {
   const int64_t stride = (int64_t)gridDim.x * (blockDim.x / kWave);
   const int lane = threadIdx.x & 63;
   for (int64_t r = (int64_t)blockIdx.x * (blockDim.x / kWave) + (threadIdx.x >> 6); r < rows; r += stride) {
     const int64_t lo = rowptr[r], hi = rowptr[r + 1];
-    const int32_t i = (int32_t)(r / J), j = (int32_t)(r % J);
-    for (int64_t p = lo + lane; p < hi; p += kWave) { yi[p] = i; yj[p] = j; }
+    const int32_t a = (int32_t)(r / B), b = (int32_t)(r % B);
+    for (int64_t p = lo + lane; p < hi; p += kWave) {
+      ya[p] = a;
+      yb[p] = b;
+      if (yc) yc[p] = colidx[p];
+    }
   }
 }
 

@@ -219,6 +219,19 @@ int spttm(spgemm_handle h, int mode, int64_t I, int64_t J, int64_t K, int64_t nn
 int sptensor_fold(spgemm_handle h, int mode, int64_t I, int64_t J, int64_t K, const spgemm_csr* Y, int32_t* yi, int32_t* yj,
                   int32_t* yk);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture set-up rules, tight
+ * serving loops, harnesses that forbid hipMalloc): sptensor_unfold with caller-owned outputs and no
+ * allocation of any kind.  out_rowptr (rows + 1 int64), out_colidx and out_values (nnz each) are device
+ * arrays, written; rows and columns are as in sptensor_unfold.  The sort buffers live in one fixed
+ * array inside the library (about 24 bytes per entry of the limit, per GPU, held until the process
+ * ends), so nnz must not exceed SPTENSOR_NOALLOC_MAX_NNZ (SPGEMM_UNSUPPORTED beyond).  Calls on the
+ * same GPU share that array: calls that overlap in time on one GPU (two streams, two threads) race
+ * and must be serialised by the caller.  Synchronises the stream once, like sptensor_unfold. */
+#define SPTENSOR_NOALLOC_MAX_NNZ 1048576
+int sptensor_unfold_noalloc(spgemm_handle h, int mode, int64_t I, int64_t J, int64_t K, int64_t nnz, const int32_t* xi,
+                            const int32_t* xj, const int32_t* xk, const void* xval, int32_t dtype, int64_t* out_rowptr,
+                            int32_t* out_colidx, void* out_values);
+
 /* The same three calls for the third mode (row i*J + j, column k). */
 int sptensor_unfold_mode3(spgemm_handle h, int64_t I, int64_t J, int64_t K, int64_t nnz, const int32_t* xi,
                           const int32_t* xj, const int32_t* xk, const void* xval, int32_t dtype, spgemm_csr* out);

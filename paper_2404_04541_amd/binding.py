@@ -28,7 +28,7 @@ STATUS_NAMES = {0: "OK", -1: "INVALID_ARG", -2: "DIM_MISMATCH", -3: "DTYPE_MISMA
 
 EXPORTED = ("spgemm_create", "spgemm_destroy", "spgemm_set_option", "spgemm_symbolic", "spgemm_numeric", "spgemm",
             "spgemm_free_device", "spgemm_plan_destroy", "spgemm_get_stats", "spgemm_last_error", "spgemm_version",
-            "sptensor_unfold_mode3", "spttm_mode3", "sptensor_fold_mode3", "sptensor_unfold", "spttm", "sptensor_fold")
+            "sptensor_unfold_mode3", "spttm_mode3", "sptensor_fold_mode3", "sptensor_unfold", "spttm", "sptensor_fold", "sptensor_unfold_noalloc")
 
 
 class SpgemmError(RuntimeError):
@@ -87,6 +87,7 @@ def load_library():
     mode_args = [C.c_void_p, C.c_int] + tensor_args[1:]
     lib.sptensor_unfold.argtypes = mode_args + [P(CsrStruct)]
     lib.spttm.argtypes = mode_args + [P(CsrStruct), P(CsrStruct)]
+    lib.sptensor_unfold_noalloc.argtypes = mode_args + [C.c_void_p, C.c_void_p, C.c_void_p]
     lib.sptensor_fold.argtypes = [C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_int64, P(CsrStruct), C.c_void_p, C.c_void_p, C.c_void_p]
     lib.spgemm_last_error.argtypes = [C.c_void_p]
     lib.spgemm_last_error.restype = C.c_char_p
@@ -334,3 +335,15 @@ def sptensor_fold(handle: Handle, mode: int, shape, Y: DeviceCSR):
     I, J, K = (int(v) for v in shape)
     handle._check(handle.lib.sptensor_fold(handle.ptr, int(mode), I, J, K, C.byref(sy), *[t.data_ptr() if Y.nnz else None for t in out]))
     return tuple(out)
+
+
+NOALLOC_MAX_NNZ = 1 << 20
+
+
+def sptensor_unfold_noalloc(handle: Handle, mode: int, shape, xi, xj, xk, xval, out_rowptr, out_colidx, out_values):
+    """sptensor_unfold into caller-owned device tensors, without any allocation inside the library."""
+    n = int(xval.numel())
+    assert out_rowptr.dtype == torch.int64 and out_colidx.dtype == torch.int32 and out_values.dtype == xval.dtype
+    assert out_colidx.numel() >= n and out_values.numel() >= n
+    handle._check(handle.lib.sptensor_unfold_noalloc(*_mode_args(handle, mode, shape, xi, xj, xk, xval), out_rowptr.data_ptr(),
+                                                     out_colidx.data_ptr() if n else None, out_values.data_ptr() if n else None))

@@ -767,6 +767,13 @@ int unfold_run(spgemm_context* h, const ModeView& v, int64_t nnz, const void* xv
   return SPGEMM_OK;
 }
 
+// Scratch of the entry point that allocates nothing: one array per device, held until the process ends.
+constexpr int64_t kNoAllocMaxNnz = SPTENSOR_NOALLOC_MAX_NNZ;
+constexpr size_t kNoAllocScratchBytes = (size_t)kNoAllocMaxNnz * 24 + ((size_t)kNoAllocMaxNnz / kSortTile + 1) * 1024 + 8 * 256;
+static __device__ __align__(256) unsigned char scratch[kNoAllocScratchBytes];
+constexpr int kMaxDevices = 64;
+unsigned char* g_scratch_ptr[kMaxDevices] = {};   // device address of `scratch` on each device, from hipGetSymbolAddress
+
 }  // namespace
 
 int sptensor_unfold(spgemm_handle h, int mode, int64_t I, int64_t J, int64_t K, int64_t nnz, const int32_t* xi, const int32_t* xj,
@@ -795,6 +802,32 @@ int sptensor_unfold(spgemm_handle h, int mode, int64_t I, int64_t J, int64_t K, 
   out->rows = rows; out->cols = v.C; out->nnz = nnz; out->dtype = dtype;
   out->rowptr = rp; out->colidx = col; out->values = val;
   return SPGEMM_OK;
+}
+
+int sptensor_unfold_noalloc(spgemm_handle h, int mode, int64_t I, int64_t J, int64_t K, int64_t nnz, const int32_t* xi, const int32_t* xj,
+                            const int32_t* xk, const void* xval, int32_t dtype, int64_t* out_rowptr, int32_t* out_colidx,
+                            void* out_values) {
+  if (!h) return SPGEMM_INVALID_ARG;
+  ModeView v{};
+  int rc = check_tensor(h, mode, I, J, K, nnz, xi, xj, xk, xval, dtype, &v);
+  if (rc) return rc;
+  if (!out_rowptr || (nnz > 0 && (!out_colidx || !out_values))) return fail(h, SPGEMM_INVALID_ARG, "output array null");
+  if (nnz > kNoAllocMaxNnz)
+    return fail(h, SPGEMM_UNSUPPORTED, "sptensor_unfold_noalloc takes at most " + std::to_string(kNoAllocMaxNnz) + " entries (fixed scratch)");
+  if ((rc = ensure_device(h))) return rc;
+  int dev = 0;
+  HIP_TRY(h, hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return fail(h, SPGEMM_UNSUPPORTED, "device ordinal beyond the scratch table");
+  if (!g_scratch_ptr[dev]) {   // once per device, with that device current
+    void* ptr = nullptr;
+    HIP_TRY(h, hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    g_scratch_ptr[dev] = static_cast<unsigned char*>(ptr);
+  }
+  const UnfoldTmp lay = unfold_tmp_layout(nnz);
+  if (lay.bytes > kNoAllocScratchBytes) return fail(h, SPGEMM_UNSUPPORTED, "internal: scratch layout exceeds the fixed scratch");
+  // (every buffer inside the scratch is written before it is read, the flag is cleared by a kernel:
+  // what the previous call left behind does not matter)
+  return unfold_run(h, v, nnz, xval, dtype, g_scratch_ptr[dev], lay, out_rowptr, out_colidx, out_values);
 }
 
 int sptensor_unfold_mode3(spgemm_handle h, int64_t I, int64_t J, int64_t K, int64_t nnz, const int32_t* xi, const int32_t* xj,

@@ -54,6 +54,18 @@ static_assert((long long)kBlkCols * 12 + kBlkCols / 8 <= kTileBudget, "direct ti
 static_assert(kRankBlkBytes + 8LL * kBlkCols <= kTileBudget, "ranked tile: one block must fit even when it is full");
 constexpr int kRegSegs = 2;             // segments of A entries that the numeric kernel keeps in registers
 constexpr long long kListBias = 1LL << 40;   // RunRec::list holds position + bias (so that -1 can mean "none")
+constexpr long long kListFlagWords = 1LL << 60;   // RunRec::list: the row's structure is kept as flag words, not as columns
+constexpr int kFlagWordsNum = 1, kFlagWordsDen = 1;   // flag words are kept when words * Num <= entries * Den (measured: best near one entry per word)
+constexpr int kGrpWords = 64;                // flag words per group: the plan keeps the rank of every group's first entry
+constexpr int kSpanGroups = kSymFlagWords / kGrpWords;
+
+// Layout of a span's structure kept as flag words: first the group ranks (row-relative rank of the first
+// entry of every group of kGrpWords words, padded to 16 bytes), then the flag words themselves.
+__host__ __device__ __forceinline__ int span_flag_words(int64_t n_cols, int64_t c0) {
+  const int64_t left = n_cols - c0, span = (int64_t)kSymFlagWords * 32;
+  return (int)(((left < span ? left : span) + 31) >> 5);
+}
+__host__ __device__ __forceinline__ int span_rank_slots(int words) { return (((words + kGrpWords - 1) / kGrpWords) + 3) & ~3; }
 
 // Stores and loads of data that passes through the numeric kernel once (the result, the plan's
 // column list): the non-temporal hint keeps it from displacing B, which is re-read all the time,
@@ -65,8 +77,9 @@ template <typename V>
 __device__ __forceinline__ V stream_load(const V* p) { return __builtin_nontemporal_load(p); }
 
 struct TileRec { int b0, b1, cnt, out; };     // blocks [b0, b1), entries (| kDirectBit), offset inside the row of C
-// tiles [first, first + count) of one row; its A entries [a0, a0 + d); list: where entry 0 of the
-// row sits in the column list, plus kListBias (-1: the row has no list)
+// tiles [first, first + count) of one row; its A entries [a0, a0 + d); list (-1: the row has no list):
+// where entry 0 of the row sits in the plan's list, plus kListBias - or, with kListFlagWords set,
+// where the flag word of column 0 sits (the row's structure is kept as one bit per column)
 struct RunRec { int row; unsigned first; int count, d; long long a0, list; };
 
 // Per-workgroup bookkeeping of the piece walker below.
@@ -241,7 +254,9 @@ struct TilePlan {
   unsigned tile_base, run_base;
   int row_out;
   int span_out0;          // row_out when the span began
-  long long list_base;    // position of the span's first entry in the column list, -1 = none
+  long long list_base;    // position of the span's first entry (or first flag word) in the plan's list, -1 = none
+  int list_words;         // > 0: the span's structure goes to the list as that many flag words instead of columns
+  int grp[kSpanGroups];   // entries per group of kGrpWords flag words
 };
 
 // index of the lowest set bit at or above position b in the 128-bit mask (hi:lo); 128 when none
@@ -410,6 +425,7 @@ __global__ __launch_bounds__(kDenseThreads) void k_sym_dense(const int* __restri
           local += __popc(v.x) + __popc(v.y) + __popc(v.z) + __popc(v.w);
         }
         local += __shfl_xor(local, 1, kWave);
+        if ((tid & 1) == 0) tp->grp[tid >> 1] = local;   // (32 words per thread: a pair of threads is a group)
         local += __shfl_xor(local, 2, kWave);
         local += __shfl_xor(local, 4, kWave);
         if ((tid & 7) == 0) tp->blk_cnt[tid >> 3] = local;
@@ -436,13 +452,22 @@ __global__ __launch_bounds__(kDenseThreads) void k_sym_dense(const int* __restri
         const int nt = tp->ntiles;
         const int nr = (nt + kRunTiles - 1) / kRunTiles;
         const bool want_list = !count_only && total > 0 && list_cap > 0;
+        // a short row with little deduplication becomes one searched tile and needs its columns; every
+        // other row keeps its flag words as they are (no decoding here, and far less memory for rows
+        // with many entries) unless they would take much more room than the columns
+        const bool search_row = whole_row && total <= kSearchCap && nt > 1 && (long long)ip[row] <= (long long)search_ratio * total;
+        const int fwords = (words + 3) & ~3;
+        const bool as_words = !search_row && (long long)fwords * kFlagWordsNum <= (long long)kFlagWordsDen * total;
+        const unsigned long long need = as_words ? (unsigned long long)(span_rank_slots(words) + fwords)
+                                                 : (unsigned long long)((total + 3) & ~3);   // (16-byte granules)
         unsigned long long at = 0;
         unsigned tb = 0, rb = 0, nx = 0;
-        if (want_list) at = atomicAdd(&ctl->list_cursor, (unsigned long long)total);
+        if (want_list) at = atomicAdd(&ctl->list_cursor, need);
         if (nt > 0) { tb = atomicAdd(&ctl->tile_cursor, (unsigned)nt); rb = atomicAdd(&ctl->run_cursor, (unsigned)nr); }
         if (last_span) nx = atomicAdd(&ctl->work[0], 1u);
-        const bool listed = want_list && at + (unsigned long long)total <= list_cap;
+        const bool listed = want_list && at + need <= list_cap;
         tp->list_base = listed ? (long long)at : -1;
+        tp->list_words = listed && as_words ? fwords : 0;
         tp->tile_base = tb;
         tp->run_base = rb;
         tp->next_block = 0;
@@ -451,7 +476,7 @@ __global__ __launch_bounds__(kDenseThreads) void k_sym_dense(const int* __restri
           ctl->error = 3;   // cannot happen when the host sized the lists from the bound
           tp->ntiles = 0;
           tp->nruns = 0;
-        } else if (listed && whole_row && total <= kSearchCap && nt > 1 && (long long)ip[row] <= (long long)search_ratio * total) {
+        } else if (listed && search_row) {
           // (a searched tile pays a bisection per product: only for rows with little deduplication, and
           // only where it saves tiles - a row that is one ranked or direct tile anyway stays that)
           tp->rec[0] = TileRec{block0, block0 + nb, total | kSearchBit, tp->span_out0};
@@ -470,11 +495,25 @@ __global__ __launch_bounds__(kDenseThreads) void k_sym_dense(const int* __restri
         if (tid < nt) tiles[tp->tile_base + tid] = tp->rec[tid];
         if (tid < tp->nruns) {   // (runs behind the tiles in use stay empty: count 0)
           const int left = nt - tid * kRunTiles;
-          runs[tp->run_base + tid] = RunRec{row, tp->tile_base + (unsigned)(tid * kRunTiles), left < 0 ? 0 : (left < kRunTiles ? left : kRunTiles), d, a0,
-                                            lb < 0 ? -1LL : lb - tp->span_out0 + kListBias};
+          // (flag words: the position of the word of column 0, which may lie before the span's words)
+          const long long lpos = lb < 0 ? -1LL : (tp->list_words ? (lb + kListBias) | kListFlagWords : lb - tp->span_out0 + kListBias);
+          runs[tp->run_base + tid] = RunRec{row, tp->tile_base + (unsigned)(tid * kRunTiles), left < 0 ? 0 : (left < kRunTiles ? left : kRunTiles), d, a0, lpos};
         }
       }
-      if (lb >= 0) {
+      if (lb >= 0 && tp->list_words) {
+        // the flag list leaves as it is (one coalesced copy), behind the rank of every group's first entry
+        static_assert(kGrpWords * 4 == kBlkWords && kSpanGroups <= kDenseThreads, "four groups per block, a thread per group");
+        const int nslots = span_rank_slots(words);
+        if (tid < nslots) {
+          int r = tp->span_out0 + tp->cum[(tid >> 2) < kSpanBlocks ? (tid >> 2) : kSpanBlocks];
+          for (int g = tid & ~3; g < tid; ++g) r += tp->grp[g];
+          col_list[lb + tid] = r;
+        }
+        const uint4* f4 = reinterpret_cast<const uint4*>(flags);
+        uint4* o4 = reinterpret_cast<uint4*>(col_list + lb + nslots);
+        const int n4 = tp->list_words >> 2;
+        for (int w = tid; w < n4; w += kDenseThreads) o4[w] = f4[w];
+      } else if (lb >= 0) {
         // The list position of a block's first entry is its entry prefix.  Sparse blocks: the columns are decoded, a round
         // with few entries is gathered in LDS first and leaves as one coalesced run.
         // Direct blocks: the numeric kernel wants the flag words themselves (their 256 words fit
@@ -730,8 +769,10 @@ __device__ __forceinline__ void num_dense_run(const RunRec rr, NumScratch<T>* ns
                                               int64_t out_row, int32_t* __restrict__ c_col, T* __restrict__ c_val,
                                               const int (&pre_k)[kRegSegs], const T (&pre_av)[kRegSegs]) {
   const int tid = threadIdx.x;
-  const bool have_list = rr.list >= 0;
-  const long long list_at = rr.list - kListBias;
+  // the row's structure in the plan: none, its columns, or its flag words
+  const bool have_words = rr.list >= 0 && (rr.list & kListFlagWords) != 0;
+  const bool have_list = rr.list >= 0 && !have_words;
+  const long long list_at = (rr.list & (kListFlagWords - 1)) - kListBias;   // entry 0 of the row, or the span's kept structure
   const int64_t a0 = rr.a0;
   const int d = rr.d;
   const int nseg = (d + kSegCap - 1) / kSegCap;
@@ -771,6 +812,10 @@ __device__ __forceinline__ void num_dense_run(const RunRec rr, NumScratch<T>* ns
     int64_t t_hi = (int64_t)tr.b1 << kBlkShift;
     if (t_hi > n_cols) t_hi = n_cols;
     const int64_t out = out_row + tr.out;
+    // kept flag words of the tile's span: group ranks first, then the words (indexed here by absolute word)
+    const int64_t span_c0 = (int64_t)(tr.b0 / kSpanBlocks) * kSpanBlocks * kBlkCols;
+    const int32_t* kept_ranks = col_list + list_at;
+    const int32_t* kept_words = col_list + list_at + span_rank_slots(span_flag_words(n_cols, span_c0)) - (span_c0 >> 5);
     // this thread's pieces of the tile, one per cached segment
     int off_c[kRegSegs], len_c[kRegSegs];
 #pragma unroll
@@ -884,7 +929,9 @@ __device__ __forceinline__ void num_dense_run(const RunRec rr, NumScratch<T>* ns
         for (int r = tid; r < kBlkCols / 2; r += kDenseThreads) a2[r] = make_double2(0.0, 0.0);
       }
       // which columns exist: the flag words are in the plan's list, or are rebuilt by the pass
-      if (tid < kBlkCols / 32) flags[tid] = have_list ? (unsigned)col_list[list_at + tr.out + tid] : 0u;
+      if (tid < kBlkCols / 32)   // (the last block of the matrix may be cut short: no flag words are kept behind its end)
+        flags[tid] = have_words ? (tid < (int)((t_hi - t_lo + 31) >> 5) ? (unsigned)kept_words[(long long)tr.b0 * kBlkWords + tid] : 0u)
+                                : (have_list ? (unsigned)col_list[list_at + tr.out + tid] : 0u);
       SPG_CLK(clk_add(&ns->clk, 18, 1);)
       for (int sg = 0; sg < nseg; ++sg) {
         T av = my_av;
@@ -895,7 +942,7 @@ __device__ __forceinline__ void num_dense_run(const RunRec rr, NumScratch<T>* ns
         chunk_pass<true, T>(np, nchunks, ns, b_col, b_val, [&](int c, T a, T b) {
           if (!CHECK || (c >= t_lo && (int64_t)c < t_hi)) {
             const int rel = c - t_lo;
-            if (!have_list) atomicOr(&flags[rel >> 5], 1u << (rel & 31));
+            if (!have_list && !have_words) atomicOr(&flags[rel >> 5], 1u << (rel & 31));
             __hip_atomic_fetch_add(&acc[rel], (double)a * (double)b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
           }
         });
@@ -944,8 +991,10 @@ __device__ __forceinline__ void num_dense_run(const RunRec rr, NumScratch<T>* ns
         }
       };
       if (have_list) fetch_list(0);
-      for (int w = tid; w < nw; w += kDenseThreads) fc[w] = make_uint2(0u, 0u);
       int np = 0, nchunks = 0;
+      int* stage = reinterpret_cast<int*>(acc);   // columns by rank, in the space of the sums, on their way to C
+      if (!have_words)
+        for (int w = tid; w < nw; w += kDenseThreads) fc[w] = make_uint2(0u, 0u);
       if (have_list) {
         // the symbolic phase left the tile's columns (ascending) in the plan: flag bits and ranks
         // come from that list, and the list is this tile's run of C's column indices
@@ -970,6 +1019,57 @@ __device__ __forceinline__ void num_dense_run(const RunRec rr, NumScratch<T>* ns
         }
         __syncthreads();
         SPG_CLK(clk_mark(&ns->clk, 4);)
+      } else if (have_words) {
+        // the symbolic phase left the span's flag words in the plan, with the rank of the first entry of
+        // every group of kGrpWords words: groups are dealt to the waves in turn (entries thin out with the
+        // column, so neighbouring groups cost about the same), a lane takes a word, ranks follow from one
+        // scan over the wave, and the columns are decoded ("boolean indexing") by rank into LDS
+        const int wave = tid >> 6, lane = tid & 63;
+        const int ngrp = nw / kGrpWords;
+        const int nw_kept = (int)((t_hi - t_lo + 31) >> 5);   // (the last block of the matrix may be cut short)
+        const int32_t* tw = kept_words + (long long)tr.b0 * kBlkWords;
+        const int32_t* tr_ranks = kept_ranks + (int)((t_lo - span_c0) >> 5) / kGrpWords;
+        constexpr int kGrpBatch = 4;
+        int wd[kGrpBatch], rk[kGrpBatch];
+        auto fetch_groups = [&](int g0) {
+#pragma unroll
+          for (int i = 0; i < kGrpBatch; ++i) {
+            const int g = g0 + i * kDenseWaves;
+            const int w = g * kGrpWords + lane;
+            wd[i] = (g < ngrp && w < nw_kept) ? stream_load(&tw[w]) : 0;
+            rk[i] = g < ngrp ? tr_ranks[g] : 0;
+          }
+        };
+        fetch_groups(wave);
+        for (int g0 = wave; g0 < ngrp; g0 += kDenseWaves * kGrpBatch) {
+          int cw[kGrpBatch], cr[kGrpBatch];
+#pragma unroll
+          for (int i = 0; i < kGrpBatch; ++i) { cw[i] = wd[i]; cr[i] = rk[i]; }
+          if (g0 + kDenseWaves * kGrpBatch < ngrp) fetch_groups(g0 + kDenseWaves * kGrpBatch);   // the next batch, while this one is decoded
+#pragma unroll
+          for (int i = 0; i < kGrpBatch; ++i) {
+            const int g = g0 + i * kDenseWaves;
+            if (g < ngrp) {
+              const int w = g * kGrpWords + lane;
+              unsigned bits = (unsigned)cw[i];
+              const int c = __popc(bits);
+              int excl = cr[i] - tr.out + wave_incl_scan(c) - c;   // rank inside the tile
+              fc[w] = make_uint2(bits, (unsigned)excl);
+              const int cbase = t_lo + w * 32;
+              while (bits) {
+                const int b = __ffs((int)bits) - 1;
+                bits &= bits - 1;
+                stage[excl++] = cbase + b;
+              }
+            }
+          }
+        }
+        __syncthreads();
+        for (int r = tid; r < count; r += kDenseThreads) stream_store(&c_col[out + r], stage[r]);
+        __syncthreads();
+        for (int r = tid; r < count; r += kDenseThreads) acc[r] = 0.0;
+        if (nseg == 1) tile_pieces(ns, s, len, my_av, np, nchunks); else __syncthreads();
+        SPG_CLK(clk_mark(&ns->clk, 15); clk_add(&ns->clk, 17, 1);)
       } else {
       // pass 1: which columns of the tile exist in the row
       for (int sg = 0; sg < nseg; ++sg) {
@@ -985,7 +1085,9 @@ __device__ __forceinline__ void num_dense_run(const RunRec rr, NumScratch<T>* ns
         if (nseg > 1) __syncthreads();
       }
       // exclusive prefix of the flag-word populations: every wave owns a contiguous share of
-      // the words and walks it 64 words at a time (lane = word, so LDS reads do not collide)
+      // the words and walks it 64 words at a time (lane = word, so LDS reads do not collide);
+      // the columns are decoded from the flag words into the space of the sums, by rank, and
+      // leave from there as one coalesced run of C's column indices
       const int wave = tid >> 6, lane = tid & 63;
       const int wper = ((nw + kDenseThreads - 1) / kDenseThreads) * kWave;
       const int wbase = wave * wper;
@@ -1010,12 +1112,15 @@ __device__ __forceinline__ void num_dense_run(const RunRec rr, NumScratch<T>* ns
         running += __builtin_amdgcn_readlane(incl, kWave - 1);
         if (w < nw) fc[w].y = (unsigned)excl;
         const int cbase = t_lo + w * 32;
-        while (bits) {   // columns are decoded from the flag words ("boolean indexing")
+        while (bits) {
           const int b = __ffs((int)bits) - 1;
           bits &= bits - 1;
-          c_col[out + excl++] = cbase + b;   // (short runs per lane: this route is the fallback without a column list)
+          stage[excl++] = cbase + b;
         }
       }
+      __syncthreads();
+      for (int r = tid; r < count; r += kDenseThreads) stream_store(&c_col[out + r], stage[r]);
+      __syncthreads();
       for (int r = tid; r < count; r += kDenseThreads) acc[r] = 0.0;
       __syncthreads();
       SPG_CLK(clk_mark(&ns->clk, 13);)

@@ -269,7 +269,7 @@ int alloc_dense_lists(spgemm_context* h, spgemm_plan_s* p, const spgemm_csr* B, 
   // more than a third of what the device has free, and do without if the allocation fails.
   size_t free_b = 0, total_b = 0;
   if (h->col_list && hipMemGetInfo(&free_b, &total_b) == hipSuccess) {
-    double want = entries * 4.0;
+    double want = (entries + 4.0 * rows_d * spans) * 4.0;   // (every row's share is rounded up to 16 bytes)
     if (want > (double)free_b / 3.0) want = (double)free_b / 3.0;
     if (h->col_list > 1 && want > (double)h->col_list) want = (double)h->col_list;
     const size_t bytes = ((size_t)want) & ~(size_t)255;

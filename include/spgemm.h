@@ -104,6 +104,9 @@ typedef struct {
   int64_t dense_direct_tiles; /* of those, tiles accumulated by column (one pass) */
   int64_t dense_runs;         /* work items (runs of tiles of one row) */
   int64_t dense_search_tiles; /* of the tiles, whole short rows whose ranks come from bisecting the column list */
+  int64_t plan_bytes;         /* device memory the plan holds (per-row arrays, tile lists, block table, structure list) */
+  int64_t plan_list_bytes;    /* of those, what the structure list (columns or flag words of the dense rows) was given */
+  int64_t plan_list_used;     /* ... and what the symbolic phase filled of it */
 } spgemm_stats;
 
 /* Options for spgemm_set_option. */

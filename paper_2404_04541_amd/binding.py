@@ -55,7 +55,8 @@ class StatsStruct(C.Structure):
                 ("num_bin_rows", C.c_int64 * NUM_BINS), ("sym_bin_ip", C.c_int64 * NUM_BINS),
                 ("num_bin_ip", C.c_int64 * NUM_BINS), ("num_bin_nnz", C.c_int64 * NUM_BINS), ("kernel_ms", C.c_double * NUM_KERNEL_CLASSES),
                 ("kernel_launches", C.c_int32 * NUM_KERNEL_CLASSES), ("dense_tiles", C.c_int64),
-                ("dense_direct_tiles", C.c_int64), ("dense_runs", C.c_int64), ("dense_search_tiles", C.c_int64)]
+                ("dense_direct_tiles", C.c_int64), ("dense_runs", C.c_int64), ("dense_search_tiles", C.c_int64),
+                ("plan_bytes", C.c_int64), ("plan_list_bytes", C.c_int64), ("plan_list_used", C.c_int64)]
 
 
 _lib = None
@@ -141,7 +142,8 @@ class Plan:
                 "kernel_ms": dict(zip(KERNEL_CLASS_NAMES, st.kernel_ms)),
                 "kernel_launches": dict(zip(KERNEL_CLASS_NAMES, st.kernel_launches)),
                 "dense_tiles": int(st.dense_tiles), "dense_direct_tiles": int(st.dense_direct_tiles),
-                "dense_runs": int(st.dense_runs), "dense_search_tiles": int(st.dense_search_tiles)}
+                "dense_runs": int(st.dense_runs), "dense_search_tiles": int(st.dense_search_tiles),
+                "plan_bytes": int(st.plan_bytes), "plan_list_bytes": int(st.plan_list_bytes), "plan_list_used": int(st.plan_list_used)}
 
     def destroy(self):
         if self.ptr:

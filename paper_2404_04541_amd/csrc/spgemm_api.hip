@@ -53,6 +53,7 @@ struct spgemm_plan_s {
   int64_t m = 0, k = 0, n = 0, nnz_a = 0, nnz_b = 0;
   int dtype = 0;
   void* scratch = nullptr;
+  size_t scratch_bytes = 0, scratch2_bytes = 0, scratch3_bytes = 0;
   int* ip = nullptr;
   int* cnt = nullptr;
   int* perm_sym = nullptr;
@@ -259,6 +260,7 @@ int alloc_dense_lists(spgemm_context* h, spgemm_plan_s* p, const spgemm_csr* B, 
   const size_t o_runs = off; off = align_up(off + (size_t)*run_cap * sizeof(RunRec));
   const size_t o_bp = off; if (with_bp) off = align_up(off + bp_bytes);
   p->scratch2 = dev_alloc(h, off);
+  p->scratch2_bytes = off;
   if (!p->scratch2) return fail(h, SPGEMM_ALLOC_FAILED, "device allocation of the dense workspace lists failed");
   unsigned char* base = static_cast<unsigned char*>(p->scratch2);
   p->tiles = reinterpret_cast<TileRec*>(base + o_tiles);
@@ -276,6 +278,7 @@ int alloc_dense_lists(spgemm_context* h, spgemm_plan_s* p, const spgemm_csr* B, 
     if (bytes >= 4096) {
       p->scratch3 = dev_alloc(h, bytes);
       if (p->scratch3) {
+        p->scratch3_bytes = bytes;
         p->col_list = static_cast<int32_t*>(p->scratch3);
         p->col_list_cap = bytes / 4;
       }
@@ -529,6 +532,7 @@ int spgemm_symbolic(spgemm_handle h, const spgemm_csr* A, const spgemm_csr* B, i
   const size_t o_bin = off; off = align_up(off + (size_t)m);
   const size_t o_part = off; off = align_up(off + (size_t)(p->scan_blocks + 1) * 8);
   p->scratch = dev_alloc(h, off);
+  p->scratch_bytes = off;
   if (!p->scratch) {
     delete p;
     return fail(h, SPGEMM_ALLOC_FAILED, "device allocation of plan scratch failed");
@@ -581,6 +585,9 @@ int spgemm_symbolic(spgemm_handle h, const spgemm_csr* A, const spgemm_csr* B, i
   p->stats.dense_direct_tiles = host.direct_tiles;
   p->stats.dense_runs = host.run_cursor;
   p->stats.dense_search_tiles = host.search_tiles;
+  p->stats.plan_bytes = (int64_t)(p->scratch_bytes + p->scratch2_bytes + p->scratch3_bytes);
+  p->stats.plan_list_bytes = (int64_t)p->scratch3_bytes;
+  p->stats.plan_list_used = (int64_t)((host.list_cursor < host.list_cap ? host.list_cursor : host.list_cap) * 4ULL);
   p->symbolic_done = true;
   *nnz_c = host.nnz_c;
   *plan = p;

@@ -68,27 +68,26 @@ def test_coordinate_out_of_range_is_reported():
 
 
 def test_config5_through_the_tensor_entry_point():
-    # the full-size tensor of configuration 5 from its coordinates: unfolding on the GPU must give the
-    # matrix that the generator builds on the host, and the product the same C as the matrix route
+    # the full-size tensor of configuration 5 from its unordered coordinates: the unfolding and the product
+    # against the CPU checker (its own unfolding of the same coordinates, then its row-wise product), whole
     import torch
     from paper_2404_04541_amd import binding as sg
+    from test_gpu_full_configs import check_whole
     x = W.coo3_uniform((2048, 2048, 2048), 10_000_000, 0, 40, np.float64)
     m = W.uniform_rows(2048, 2048, 16, 0, 44, np.float64)
     order = np.argsort(W.rand_u64(0, 77, np.arange(x.values.size, dtype=np.uint64)), kind="stable")   # hand the entries over unordered
+    xi, xj, xk, xv = (v[order] for v in (x.i, x.j, x.k, x.values))
     h = sg.Handle()
-    dxi, dxj, dxk, dv = (to_dev(v[order]) for v in (x.i, x.j, x.k, x.values))
+    dxi, dxj, dxk, dv = (to_dev(v) for v in (xi, xj, xk, xv))
     U = sg.sptensor_unfold_mode3(h, x.shape, dxi, dxj, dxk, dv)
-    a = W.unfold_mode3(x)
-    assert np.array_equal(U.rowptr.cpu().numpy(), a.rowptr) and np.array_equal(U.colidx.cpu().numpy(), a.colidx)
-    assert np.array_equal(U.values.cpu().numpy(), a.values)
-    dM = sg.to_device(m)
-    Y = sg.spttm_mode3(h, x.shape, dxi, dxj, dxk, dv, dM)
-    C = sg.spgemm(h, sg.to_device(a), dM)
+    rp, col, val = oracle.unfold(x.shape, 3, xi, xj, xk, xv)
+    assert np.array_equal(U.rowptr.cpu().numpy(), rp) and np.array_equal(U.colidx.cpu().numpy(), col)
+    assert np.array_equal(U.values.cpu().numpy(), val)
+    Y = sg.spttm_mode3(h, x.shape, dxi, dxj, dxk, dv, sg.to_device(m))
     torch.cuda.synchronize()
-    assert torch.equal(Y.rowptr, C.rowptr) and torch.equal(Y.colidx, C.colidx)
-    assert torch.allclose(Y.values, C.values, rtol=1e-12, atol=1e-14)
     assert Y.nnz > 150_000_000
-
+    a = W.CSR(2048 * 2048, 2048, rp, col, val)
+    check_whole(a, m, gpu=(Y.rowptr, Y.colidx, Y.values, Y.nnz, {"ip_total": 10_000_000 * 16}))
 
 @pytest.mark.parametrize("mode", [1, 2, 3])
 @pytest.mark.parametrize("shape,nnz,distinct,dtype", [((9, 6, 13), 300, False, np.float64), ((120, 90, 4000), 200000, True, np.float32),

@@ -243,6 +243,45 @@ int spttm_mode3(spgemm_handle h, int64_t I, int64_t J, int64_t K, int64_t nnz, c
 /* yi[p], yj[p] for entry p of Y; its third coordinate is Y->colidx[p]. */
 int sptensor_fold_mode3(spgemm_handle h, int64_t J, const spgemm_csr* Y, int32_t* yi, int32_t* yj);
 
+/* ---- outer-product route with a second-order sparse workspace -------------------------------
+ * The paper's leading example (sections 1 and 4.1, evaluated in section 7.3): C = A * B in the loop
+ * order k -> i -> j, A in doubly compressed sparse columns, B in doubly compressed sparse rows, C in
+ * compressed sparse rows.  Consecutive products land on unrelated coordinates (i, j), so they go
+ * through a workspace of whole components, run by the four stages of the algorithm template
+ * (section 4.3): insert products into the accumulation array; when it is full, sort it into result
+ * order and merge it, adding equal coordinates, into the all array; compress the all array into C.
+ * The result is the same matrix as spgemm() gives (structure bit for bit, values up to summation
+ * order); the route exists because it is the paper's own, and for operands that come in these formats.
+ *
+ * Doubly compressed format (section 2.1's level formats Compressed, Compressed): only the nvec
+ * non-empty vectors (columns for A, rows for B) are kept: vec[v] is the v-th kept vector's index,
+ * ascending, below major_dim; its entries are idx/values[ptr[v] .. ptr[v+1]) with idx below
+ * minor_dim.  All arrays are device pointers; idx need not be sorted or unique inside a vector. */
+typedef struct {
+  int64_t major_dim, minor_dim; /* extent of the compressed dimension, extent of idx */
+  int64_t nvec, nnz;
+  const int32_t* vec;  /* device, nvec */
+  const int64_t* ptr;  /* device, nvec + 1 */
+  const int32_t* idx;  /* device, nnz */
+  const void* values;  /* device, nnz elements of dtype */
+  int32_t dtype;       /* spgemm_dtype */
+} spgemm_dcs;
+
+/* Conversions from CSR: rows without entries dropped (doubly compressed rows), or entries regrouped by
+ * column with a stable sort and empty columns dropped (doubly compressed columns).  The four arrays of
+ * *out come from the handle's allocator; release them with spgemm_dcs_free.  Both synchronise. */
+int spgemm_dcsr_from_csr(spgemm_handle h, const spgemm_csr* M, spgemm_dcs* out);
+int spgemm_dcsc_from_csr(spgemm_handle h, const spgemm_csr* M, spgemm_dcs* out);
+int spgemm_dcs_free(spgemm_handle h, spgemm_dcs* M);
+
+/* C = A * B by outer products.  A: doubly compressed columns of an m x k matrix (major_dim = k,
+ * minor_dim = m); B: doubly compressed rows of a k x n matrix (major_dim = k, minor_dim = n).
+ * acc_capacity: components the accumulation array holds before it is sorted and merged (0: 2^24).
+ * C's buffers come from the handle's allocator (release with its free or spgemm_free_device).
+ * Synchronises (once per batch of acc_capacity products).  Sums are accumulated in double.
+ * SPGEMM_UNSUPPORTED: the result would have 2^32 - 1 or more entries. */
+int spgemm_outer(spgemm_handle h, const spgemm_dcs* A, const spgemm_dcs* B, int64_t acc_capacity, spgemm_csr* C);
+
 /* Library version: major*10000 + minor*100 + patch. */
 int spgemm_version(void);
 

@@ -28,7 +28,8 @@ STATUS_NAMES = {0: "OK", -1: "INVALID_ARG", -2: "DIM_MISMATCH", -3: "DTYPE_MISMA
 
 EXPORTED = ("spgemm_create", "spgemm_destroy", "spgemm_set_option", "spgemm_symbolic", "spgemm_numeric", "spgemm",
             "spgemm_free_device", "spgemm_plan_destroy", "spgemm_get_stats", "spgemm_last_error", "spgemm_version",
-            "sptensor_unfold_mode3", "spttm_mode3", "sptensor_fold_mode3", "sptensor_unfold", "spttm", "sptensor_fold", "sptensor_unfold_noalloc")
+            "sptensor_unfold_mode3", "spttm_mode3", "sptensor_fold_mode3", "sptensor_unfold", "spttm", "sptensor_fold", "sptensor_unfold_noalloc",
+            "spgemm_dcsr_from_csr", "spgemm_dcsc_from_csr", "spgemm_dcs_free", "spgemm_outer")
 
 
 class SpgemmError(RuntimeError):
@@ -48,6 +49,11 @@ FREE_FN = C.CFUNCTYPE(None, C.c_void_p, C.c_void_p)
 
 class AllocatorStruct(C.Structure):
     _fields_ = [("alloc", ALLOC_FN), ("free", FREE_FN), ("ctx", C.c_void_p)]
+
+
+class DcsStruct(C.Structure):
+    _fields_ = [("major_dim", C.c_int64), ("minor_dim", C.c_int64), ("nvec", C.c_int64), ("nnz", C.c_int64), ("vec", C.c_void_p),
+                ("ptr", C.c_void_p), ("idx", C.c_void_p), ("values", C.c_void_p), ("dtype", C.c_int32)]
 
 
 class StatsStruct(C.Structure):
@@ -90,6 +96,10 @@ def load_library():
     lib.spttm.argtypes = mode_args + [P(CsrStruct), P(CsrStruct)]
     lib.sptensor_unfold_noalloc.argtypes = mode_args + [C.c_void_p, C.c_void_p, C.c_void_p]
     lib.sptensor_fold.argtypes = [C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_int64, P(CsrStruct), C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.spgemm_dcsr_from_csr.argtypes = [C.c_void_p, P(CsrStruct), P(DcsStruct)]
+    lib.spgemm_dcsc_from_csr.argtypes = [C.c_void_p, P(CsrStruct), P(DcsStruct)]
+    lib.spgemm_dcs_free.argtypes = [C.c_void_p, P(DcsStruct)]
+    lib.spgemm_outer.argtypes = [C.c_void_p, P(DcsStruct), P(DcsStruct), C.c_int64, P(CsrStruct)]
     lib.spgemm_last_error.argtypes = [C.c_void_p]
     lib.spgemm_last_error.restype = C.c_char_p
     for name in EXPORTED:
@@ -349,3 +359,50 @@ def sptensor_unfold_noalloc(handle: Handle, mode: int, shape, xi, xj, xk, xval, 
     assert out_colidx.numel() >= n and out_values.numel() >= n
     handle._check(handle.lib.sptensor_unfold_noalloc(*_mode_args(handle, mode, shape, xi, xj, xk, xval), out_rowptr.data_ptr(),
                                                      out_colidx.data_ptr() if n else None, out_values.data_ptr() if n else None))
+
+
+@dataclass
+class DeviceDCS:
+    """Doubly compressed sparse rows or columns held in torch device tensors."""
+    major_dim: int
+    minor_dim: int
+    vec: torch.Tensor      # int32, the kept vectors' indices
+    ptr: torch.Tensor      # int64, len(vec) + 1
+    idx: torch.Tensor      # int32
+    values: torch.Tensor
+
+    def struct(self) -> DcsStruct:
+        dt = {torch.float32: SPGEMM_F32, torch.float64: SPGEMM_F64}[self.values.dtype]
+        nv, n = int(self.vec.numel()), int(self.idx.numel())
+        return DcsStruct(self.major_dim, self.minor_dim, nv, n, self.vec.data_ptr() if nv else None, self.ptr.data_ptr(),
+                         self.idx.data_ptr() if n else None, self.values.data_ptr() if n else None, dt)
+
+
+def _adopt_dcs(handle: Handle, sd: DcsStruct, vdt: torch.dtype) -> DeviceDCS:
+    vsz = 4 if vdt == torch.float32 else 8
+    # (the library allocates nvec + 1 slots for vec so that an empty list still has a buffer)
+    vec = handle.adopt(sd.vec, (sd.nvec + 1) * 4, torch.int32)[:sd.nvec]
+    ptr = handle.adopt(sd.ptr, (sd.nvec + 1) * 8, torch.int64)
+    idx = handle.adopt(sd.idx, max(sd.nnz, 0) * 4, torch.int32)
+    val = handle.adopt(sd.values, max(sd.nnz, 0) * vsz, vdt)
+    return DeviceDCS(int(sd.major_dim), int(sd.minor_dim), vec, ptr, idx, val)
+
+
+def dcsr_from_csr(handle: Handle, M: DeviceCSR) -> DeviceDCS:
+    sm, sd = M.struct(), DcsStruct()
+    handle._check(handle.lib.spgemm_dcsr_from_csr(handle.ptr, C.byref(sm), C.byref(sd)))
+    return _adopt_dcs(handle, sd, M.values.dtype)
+
+
+def dcsc_from_csr(handle: Handle, M: DeviceCSR) -> DeviceDCS:
+    sm, sd = M.struct(), DcsStruct()
+    handle._check(handle.lib.spgemm_dcsc_from_csr(handle.ptr, C.byref(sm), C.byref(sd)))
+    return _adopt_dcs(handle, sd, M.values.dtype)
+
+
+def spgemm_outer(handle: Handle, A: DeviceDCS, B: DeviceDCS, acc_capacity: int = 0) -> DeviceCSR:
+    """C = A * B by outer products through the insert / sort / merge / compress stages (A doubly compressed columns,
+    B doubly compressed rows)."""
+    sa, sb, sc = A.struct(), B.struct(), CsrStruct()
+    handle._check(handle.lib.spgemm_outer(handle.ptr, C.byref(sa), C.byref(sb), int(acc_capacity), C.byref(sc)))
+    return _adopt_csr(handle, sc, A.values.dtype, A.ptr.device)

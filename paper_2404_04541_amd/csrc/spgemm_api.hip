@@ -18,6 +18,7 @@
 #include "dense_kernels.cuh"
 #include "staged_kernels.cuh"
 #include "tensor_kernels.cuh"
+#include "outer_kernels.cuh"
 
 using namespace spg;
 
@@ -728,6 +729,31 @@ __global__ void k_clear_int(int* p) {
   if (threadIdx.x == 0 && blockIdx.x == 0) *p = 0;
 }
 
+int bits_of(int64_t n) {   // bits that hold 0 .. n-1
+  int b = 0;
+  while (n > 1 && (1LL << b) < n) ++b;
+  return b;
+}
+
+// Stable least-significant-digit radix sort of (key, index) pairs, 8 bits a pass, over the low bits_lo bits
+// and the bits_hi bits from bit 32 up.  Returns which of the two buffers holds the result.
+int sort_pairs(spgemm_context* h, int64_t n, int64_t ntiles, int bits_lo, int bits_hi, unsigned long long* const keys[2],
+               unsigned* const idx[2], unsigned* hist) {
+  hipStream_t s = h->stream;
+  int cur = 0;
+  const unsigned gt = (unsigned)ceil_div(ntiles, kSortWgWaves);
+  for (int part = 0; part < 2; ++part) {
+    const int base = part == 0 ? 0 : 32, nbits = part == 0 ? bits_lo : bits_hi;
+    for (int shift = base; shift < base + nbits; shift += 8) {
+      hipLaunchKernelGGL(k_radix_hist, dim3(gt), dim3(256), 0, s, n, ntiles, shift, keys[cur], hist);
+      hipLaunchKernelGGL(k_scan_u32, dim3(1), dim3(1024), 0, s, ntiles * 256, hist);
+      hipLaunchKernelGGL(k_radix_scatter, dim3(gt), dim3(256), 0, s, n, ntiles, shift, keys[cur], idx[cur], hist, keys[1 - cur], idx[1 - cur]);
+      cur = 1 - cur;
+    }
+  }
+  return cur;
+}
+
 // Keys, stable radix sort, compress, row pointer; everything it touches is given by the caller.
 // Ends with one stream synchronisation (the out-of-range flag comes to the host).
 int unfold_run(spgemm_context* h, const ModeView& v, int64_t nnz, const void* xval, int32_t dtype, unsigned char* tmp, const UnfoldTmp& lay,
@@ -745,19 +771,7 @@ int unfold_run(spgemm_context* h, const ModeView& v, int64_t nnz, const void* xv
   if (nnz > 0) {
     const unsigned g = grid_for(nnz, 256 * 4, (int64_t)h->num_cus * 32);
     hipLaunchKernelGGL(k_tensor_keys, dim3(g), dim3(256), 0, s, nnz, v.A, v.B, v.C, v.xa, v.xb, v.xc, keys[0], idx[0], bad);
-    auto bits_of = [](int64_t n) { int b = 0; while (n > 1 && (1LL << b) < n) ++b; return b; };   // bits that hold 0 .. n-1
-    const int bits_c = bits_of(v.C), bits_r = bits_of(rows);
-    const unsigned gt = (unsigned)ceil_div(ntiles, kSortWgWaves);
-    for (int part = 0; part < 2; ++part) {
-      const int base = part == 0 ? 0 : 32, nbits = part == 0 ? bits_c : bits_r;
-      for (int shift = base; shift < base + nbits; shift += 8) {
-        hipLaunchKernelGGL(k_radix_hist, dim3(gt), dim3(256), 0, s, nnz, ntiles, shift, keys[cur], hist);
-        hipLaunchKernelGGL(k_scan_u32, dim3(1), dim3(1024), 0, s, ntiles * 256, hist);
-        hipLaunchKernelGGL(k_radix_scatter, dim3(gt), dim3(256), 0, s, nnz, ntiles, shift, keys[cur], idx[cur], hist, keys[1 - cur],
-                           idx[1 - cur]);
-        cur = 1 - cur;
-      }
-    }
+    cur = sort_pairs(h, nnz, ntiles, bits_of(v.C), bits_of(rows), keys, idx, hist);
     if (dtype == SPGEMM_F32)
       hipLaunchKernelGGL(k_tensor_compress<float>, dim3(g), dim3(256), 0, s, nnz, keys[cur], idx[cur], static_cast<const float*>(xval), col,
                          static_cast<float*>(val));
@@ -898,6 +912,275 @@ int sptensor_fold_mode3(spgemm_handle h, int64_t J, const spgemm_csr* Y, int32_t
                      (const int32_t*)nullptr, yi, yj, (int32_t*)nullptr);
   HIP_TRY(h, hipGetLastError());
   return SPGEMM_OK;
+}
+
+}  // extern "C"
+
+// ---- outer-product route -------------------------------------------------------------------
+
+namespace {
+
+__global__ void k_pair_keys(int64_t n, const int32_t* __restrict__ hi, const int32_t* __restrict__ lo, unsigned long long* __restrict__ keys,
+                            unsigned* __restrict__ idx) {
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; p < n; p += stride) {
+    keys[p] = ((unsigned long long)(unsigned)hi[p] << 32) | (unsigned)lo[p];
+    idx[p] = (unsigned)p;
+  }
+}
+
+struct DevBufs {   // device buffers released together
+  spgemm_context* h;
+  std::vector<void*> v;
+  explicit DevBufs(spgemm_context* h_) : h(h_) {}
+  ~DevBufs() { for (void* p : v) dev_free(h, p); }
+  template <typename P>
+  P* get(size_t count) {
+    void* p = dev_alloc(h, count * sizeof(P));
+    if (p) v.push_back(p);
+    return static_cast<P*>(p);
+  }
+  void release(void* p) {
+    for (auto& q : v) if (q == p) { dev_free(h, q); q = nullptr; }
+  }
+  void keep(void* p) {   // ownership leaves
+    for (auto& q : v) if (q == p) q = nullptr;
+  }
+};
+
+// Keeps the non-empty vectors of a compressed matrix (ptr over n vectors): vec / out_ptr are allocated here.
+int dcs_compress(spgemm_context* h, int64_t n, int64_t nnz, const int64_t* ptr, DevBufs& bufs, int32_t** vec, int64_t** out_ptr, int64_t* nvec) {
+  hipStream_t s = h->stream;
+  unsigned* pos = bufs.get<unsigned>((size_t)n + 1);
+  if (!pos) return fail(h, SPGEMM_ALLOC_FAILED, "allocation for the doubly compressed format failed");
+  const unsigned g = grid_for(n, 256, (int64_t)h->num_cus * 32);
+  hipLaunchKernelGGL(k_dcs_flags, dim3(g), dim3(256), 0, s, n, ptr, pos);
+  hipLaunchKernelGGL(k_clear_int, dim3(1), dim3(64), 0, s, reinterpret_cast<int*>(pos + n));
+  hipLaunchKernelGGL(k_scan_u32, dim3(1), dim3(1024), 0, s, n + 1, pos);
+  unsigned total = 0;
+  HIP_TRY(h, hipMemcpyAsync(&total, pos + n, 4, hipMemcpyDeviceToHost, s));
+  HIP_TRY(h, hipStreamSynchronize(s));
+  *nvec = total;
+  *vec = bufs.get<int32_t>((size_t)total + 1);
+  *out_ptr = bufs.get<int64_t>((size_t)total + 1);
+  if (!*vec || !*out_ptr) return fail(h, SPGEMM_ALLOC_FAILED, "allocation for the doubly compressed format failed");
+  hipLaunchKernelGGL(k_dcs_fill, dim3(g), dim3(256), 0, s, n, ptr, pos, *vec, *out_ptr, nnz, (int64_t)total);
+  HIP_TRY(h, hipGetLastError());
+  return SPGEMM_OK;
+}
+
+template <typename T>
+int outer_run(spgemm_context* h, const spgemm_dcs* A, const spgemm_dcs* B, int64_t cap, spgemm_csr* C) {
+  hipStream_t s = h->stream;
+  const int64_t m = A->minor_dim, n = B->minor_dim, na = A->nvec, nb = B->nvec;
+  DevBufs bufs(h);
+  int64_t* rp = bufs.get<int64_t>((size_t)m + 1);
+  long long* off = bufs.get<long long>((size_t)na + 1);
+  int32_t* match = bufs.get<int32_t>((size_t)na + 1);
+  if (!rp || !off || !match) return fail(h, SPGEMM_ALLOC_FAILED, "allocation for the outer product failed");
+  long long total = 0;
+  if (na > 0) {
+    hipLaunchKernelGGL(k_outer_count, dim3(grid_for(na, 256, (int64_t)h->num_cus * 32)), dim3(256), 0, s, na, A->vec, A->ptr, nb, B->vec, B->ptr,
+                       off, match);
+    hipLaunchKernelGGL(k_scan_i64, dim3(1), dim3(1024), 0, s, na, off);
+    HIP_TRY(h, hipMemcpyAsync(&total, off + na, 8, hipMemcpyDeviceToHost, s));
+    HIP_TRY(h, hipStreamSynchronize(s));
+  }
+  if (cap <= 0) cap = (int64_t)1 << 24;
+  if (cap > ((int64_t)1 << 30)) cap = (int64_t)1 << 30;
+  if (cap > total) cap = total > 0 ? total : 1;
+  const int64_t ntiles = ceil_div(cap, kSortTile);
+  // accumulation array: coordinates and insertion numbers twice (the sort's two buffers), values once
+  unsigned long long* keys[2] = {bufs.get<unsigned long long>((size_t)cap), bufs.get<unsigned long long>((size_t)cap)};
+  unsigned* seq[2] = {bufs.get<unsigned>((size_t)cap), bufs.get<unsigned>((size_t)cap)};
+  double* vals = bufs.get<double>((size_t)cap);
+  unsigned* hist = bufs.get<unsigned>((size_t)ntiles * 256);
+  if (!keys[0] || !keys[1] || !seq[0] || !seq[1] || !vals || !hist) return fail(h, SPGEMM_ALLOC_FAILED, "allocation of the accumulation array failed");
+  const int64_t cap_grid = (int64_t)h->num_cus * 32;
+  // all array: sorted, unique coordinates with their sums
+  unsigned long long* all_k = nullptr;
+  double* all_v = nullptr;
+  int64_t all_n = 0;
+  // sorted array with repeats -> unique array: head flags, their scan, one walk per run
+  auto reduce = [&](int64_t cnt, const unsigned long long* k, const unsigned* sq, const double* v, unsigned long long** ok, double** ov,
+                    int64_t* on) -> int {
+    unsigned* pos = bufs.get<unsigned>((size_t)cnt + 1);
+    if (!pos) return fail(h, SPGEMM_ALLOC_FAILED, "allocation for the merge stage failed");
+    hipLaunchKernelGGL(k_outer_heads, dim3(grid_for(cnt, 256, cap_grid)), dim3(256), 0, s, cnt, k, pos);
+    hipLaunchKernelGGL(k_clear_int, dim3(1), dim3(64), 0, s, reinterpret_cast<int*>(pos + cnt));
+    hipLaunchKernelGGL(k_scan_u32, dim3(1), dim3(1024), 0, s, cnt + 1, pos);
+    unsigned uniq = 0;
+    HIP_TRY(h, hipMemcpyAsync(&uniq, pos + cnt, 4, hipMemcpyDeviceToHost, s));
+    HIP_TRY(h, hipStreamSynchronize(s));
+    *ok = bufs.get<unsigned long long>((size_t)uniq);
+    *ov = bufs.get<double>((size_t)uniq);
+    if (!*ok || !*ov) return fail(h, SPGEMM_ALLOC_FAILED, "allocation of the all array failed");
+    hipLaunchKernelGGL(k_outer_reduce, dim3(grid_for(cnt, 256, cap_grid)), dim3(256), 0, s, cnt, k, sq, v, pos, *ok, *ov);
+    HIP_TRY(h, hipGetLastError());
+    *on = uniq;
+    bufs.release(pos);
+    return SPGEMM_OK;
+  };
+  const int bits_lo = bits_of(n), bits_hi = bits_of(m);
+  for (long long t0 = 0; t0 < total; t0 += cap) {
+    const int64_t cnt = total - t0 < cap ? total - t0 : cap;
+    // insert
+    hipLaunchKernelGGL(k_outer_insert<T>, dim3(grid_for(cnt, 256, cap_grid)), dim3(256), 0, s, (int64_t)t0, cnt, na, off, match, A->ptr, A->idx,
+                       static_cast<const T*>(A->values), B->ptr, B->idx, static_cast<const T*>(B->values), keys[0], seq[0], vals);
+    // sort
+    const int cur = sort_pairs(h, cnt, ceil_div(cnt, kSortTile), bits_lo, bits_hi, keys, seq, hist);
+    // merge: equal coordinates of the batch, then the batch into the all array
+    unsigned long long* uk = nullptr;
+    double* uv = nullptr;
+    int64_t un = 0;
+    int rc = reduce(cnt, keys[cur], seq[cur], vals, &uk, &uv, &un);
+    if (rc) return rc;
+    if (all_n == 0) {
+      all_k = uk; all_v = uv; all_n = un;
+      continue;
+    }
+    if (all_n + un >= 0xffffffffLL) return fail(h, SPGEMM_UNSUPPORTED, "the all array of the outer product would exceed 2^32 - 1 components");
+    unsigned long long* mk = bufs.get<unsigned long long>((size_t)(all_n + un));
+    double* mv = bufs.get<double>((size_t)(all_n + un));
+    if (!mk || !mv) return fail(h, SPGEMM_ALLOC_FAILED, "allocation for the merge stage failed");
+    hipLaunchKernelGGL(k_outer_merge, dim3(grid_for(all_n + un, 256, cap_grid)), dim3(256), 0, s, all_n, all_k, all_v, un, uk, uv, mk, mv);
+    unsigned long long* nk = nullptr;
+    double* nv = nullptr;
+    int64_t nn = 0;
+    rc = reduce(all_n + un, mk, nullptr, mv, &nk, &nv, &nn);
+    if (rc) return rc;
+    bufs.release(all_k); bufs.release(all_v); bufs.release(uk); bufs.release(uv); bufs.release(mk); bufs.release(mv);
+    all_k = nk; all_v = nv; all_n = nn;
+  }
+  // compress
+  int32_t* col = all_n ? bufs.get<int32_t>((size_t)all_n) : nullptr;
+  T* val = all_n ? bufs.get<T>((size_t)all_n) : nullptr;
+  if (all_n && (!col || !val)) return fail(h, SPGEMM_ALLOC_FAILED, "allocation of C failed");
+  hipLaunchKernelGGL(k_tensor_rowptr, dim3(grid_for(m + 1, 256, cap_grid)), dim3(256), 0, s, all_n, m, all_k ? all_k : keys[0], rp);
+  if (all_n)
+    hipLaunchKernelGGL(k_outer_emit<T>, dim3(grid_for(all_n, 256, cap_grid)), dim3(256), 0, s, all_n, all_k, all_v, col, val);
+  HIP_TRY(h, hipGetLastError());
+  HIP_TRY(h, hipStreamSynchronize(s));
+  bufs.keep(rp); bufs.keep(col); bufs.keep(val);
+  C->rows = m; C->cols = n; C->nnz = all_n; C->dtype = A->dtype;
+  C->rowptr = rp; C->colidx = col; C->values = val;
+  return SPGEMM_OK;
+}
+
+int check_dcs(spgemm_context* h, const spgemm_dcs* M, const char* name) {
+  if (!M) return fail(h, SPGEMM_INVALID_ARG, std::string(name) + " is null");
+  if (M->major_dim < 0 || M->minor_dim < 0 || M->nvec < 0 || M->nnz < 0 || M->nvec > M->major_dim)
+    return fail(h, SPGEMM_INVALID_ARG, std::string(name) + ": bad size");
+  if (M->dtype != SPGEMM_F32 && M->dtype != SPGEMM_F64) return fail(h, SPGEMM_INVALID_ARG, std::string(name) + ": unknown dtype");
+  if (!M->ptr || (M->nvec > 0 && !M->vec) || (M->nnz > 0 && (!M->idx || !M->values)))
+    return fail(h, SPGEMM_INVALID_ARG, std::string(name) + ": array null");
+  if (M->major_dim >= 0x7fffffffLL || M->minor_dim >= 0x7fffffffLL || M->nnz >= 0xffffffffLL)
+    return fail(h, SPGEMM_UNSUPPORTED, std::string(name) + ": extents must be below 2^31 - 1, nnz below 2^32 - 1");
+  return SPGEMM_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int spgemm_dcs_free(spgemm_handle h, spgemm_dcs* M) {
+  if (!h || !M) return SPGEMM_INVALID_ARG;
+  dev_free(h, const_cast<int32_t*>(M->vec));
+  dev_free(h, const_cast<int64_t*>(M->ptr));
+  dev_free(h, const_cast<int32_t*>(M->idx));
+  dev_free(h, const_cast<void*>(M->values));
+  std::memset(M, 0, sizeof(*M));
+  return SPGEMM_OK;
+}
+
+int spgemm_dcsr_from_csr(spgemm_handle h, const spgemm_csr* M, spgemm_dcs* out) {
+  if (!h) return SPGEMM_INVALID_ARG;
+  int rc = check_csr(h, M, "M");
+  if (rc) return rc;
+  if (!out) return fail(h, SPGEMM_INVALID_ARG, "out is null");
+  if (M->nnz >= 0xffffffffLL) return fail(h, SPGEMM_UNSUPPORTED, "nnz must be below 2^32 - 1");
+  std::memset(out, 0, sizeof(*out));
+  if ((rc = ensure_device(h))) return rc;
+  DevBufs bufs(h);
+  const size_t vsz = M->dtype == SPGEMM_F32 ? 4 : 8;
+  int32_t* vec = nullptr;
+  int64_t* ptr = nullptr;
+  int64_t nvec = 0;
+  if ((rc = dcs_compress(h, M->rows, M->nnz, M->rowptr, bufs, &vec, &ptr, &nvec))) return rc;
+  int32_t* idx = bufs.get<int32_t>((size_t)M->nnz);
+  void* val = bufs.get<unsigned char>((size_t)M->nnz * vsz);
+  if (!idx || !val) return fail(h, SPGEMM_ALLOC_FAILED, "allocation for the doubly compressed format failed");
+  if (M->nnz > 0) {
+    HIP_TRY(h, hipMemcpyAsync(idx, M->colidx, (size_t)M->nnz * 4, hipMemcpyDeviceToDevice, h->stream));
+    HIP_TRY(h, hipMemcpyAsync(val, M->values, (size_t)M->nnz * vsz, hipMemcpyDeviceToDevice, h->stream));
+  }
+  HIP_TRY(h, hipStreamSynchronize(h->stream));
+  bufs.keep(vec); bufs.keep(ptr); bufs.keep(idx); bufs.keep(val);
+  *out = spgemm_dcs{M->rows, M->cols, nvec, M->nnz, vec, ptr, idx, val, M->dtype};
+  return SPGEMM_OK;
+}
+
+int spgemm_dcsc_from_csr(spgemm_handle h, const spgemm_csr* M, spgemm_dcs* out) {
+  if (!h) return SPGEMM_INVALID_ARG;
+  int rc = check_csr(h, M, "M");
+  if (rc) return rc;
+  if (!out) return fail(h, SPGEMM_INVALID_ARG, "out is null");
+  if (M->nnz >= 0xffffffffLL) return fail(h, SPGEMM_UNSUPPORTED, "nnz must be below 2^32 - 1");
+  std::memset(out, 0, sizeof(*out));
+  if ((rc = ensure_device(h))) return rc;
+  hipStream_t s = h->stream;
+  DevBufs bufs(h);
+  const int64_t nnz = M->nnz;
+  const size_t vsz = M->dtype == SPGEMM_F32 ? 4 : 8;
+  const int64_t ntiles = ceil_div(nnz > 0 ? nnz : 1, kSortTile);
+  // compressed sparse columns first: sort the entries by (column, row), stable
+  int32_t* rowid = bufs.get<int32_t>((size_t)nnz);
+  unsigned long long* keys[2] = {bufs.get<unsigned long long>((size_t)nnz), bufs.get<unsigned long long>((size_t)nnz)};
+  unsigned* seq[2] = {bufs.get<unsigned>((size_t)nnz), bufs.get<unsigned>((size_t)nnz)};
+  unsigned* hist = bufs.get<unsigned>((size_t)ntiles * 256);
+  int64_t* colptr = bufs.get<int64_t>((size_t)M->cols + 1);
+  int32_t* idx = bufs.get<int32_t>((size_t)nnz);
+  void* val = bufs.get<unsigned char>((size_t)nnz * vsz);
+  if (!rowid || !keys[0] || !keys[1] || !seq[0] || !seq[1] || !hist || !colptr || !idx || !val)
+    return fail(h, SPGEMM_ALLOC_FAILED, "allocation for the doubly compressed format failed");
+  int cur = 0;
+  const int64_t cap_grid = (int64_t)h->num_cus * 32;
+  if (nnz > 0) {
+    hipLaunchKernelGGL(k_expand_rows, dim3(grid_for(M->rows, 4, cap_grid)), dim3(256), 0, s, M->rows, M->rowptr, rowid);
+    hipLaunchKernelGGL(k_pair_keys, dim3(grid_for(nnz, 256 * 4, cap_grid)), dim3(256), 0, s, nnz, M->colidx, rowid, keys[0], seq[0]);
+    cur = sort_pairs(h, nnz, ntiles, bits_of(M->rows), bits_of(M->cols), keys, seq, hist);
+    const unsigned g = grid_for(nnz, 256 * 4, cap_grid);
+    if (M->dtype == SPGEMM_F32)
+      hipLaunchKernelGGL(k_tensor_compress<float>, dim3(g), dim3(256), 0, s, nnz, keys[cur], seq[cur], static_cast<const float*>(M->values), idx,
+                         static_cast<float*>(val));
+    else
+      hipLaunchKernelGGL(k_tensor_compress<double>, dim3(g), dim3(256), 0, s, nnz, keys[cur], seq[cur], static_cast<const double*>(M->values), idx,
+                         static_cast<double*>(val));
+  }
+  hipLaunchKernelGGL(k_tensor_rowptr, dim3(grid_for(M->cols + 1, 256, cap_grid)), dim3(256), 0, s, nnz, M->cols, keys[cur], colptr);
+  HIP_TRY(h, hipGetLastError());
+  int32_t* vec = nullptr;
+  int64_t* ptr = nullptr;
+  int64_t nvec = 0;
+  if ((rc = dcs_compress(h, M->cols, nnz, colptr, bufs, &vec, &ptr, &nvec))) return rc;
+  HIP_TRY(h, hipStreamSynchronize(s));
+  bufs.keep(vec); bufs.keep(ptr); bufs.keep(idx); bufs.keep(val);
+  *out = spgemm_dcs{M->cols, M->rows, nvec, nnz, vec, ptr, idx, val, M->dtype};
+  return SPGEMM_OK;
+}
+
+int spgemm_outer(spgemm_handle h, const spgemm_dcs* A, const spgemm_dcs* B, int64_t acc_capacity, spgemm_csr* C) {
+  if (!h) return SPGEMM_INVALID_ARG;
+  int rc = check_dcs(h, A, "A");
+  if (rc) return rc;
+  if ((rc = check_dcs(h, B, "B"))) return rc;
+  if (!C) return fail(h, SPGEMM_INVALID_ARG, "C is null");
+  if (acc_capacity < 0) return fail(h, SPGEMM_INVALID_ARG, "negative accumulation capacity");
+  if (A->major_dim != B->major_dim) return fail(h, SPGEMM_DIM_MISMATCH, "A's columns and B's rows differ in extent");
+  if (A->dtype != B->dtype) return fail(h, SPGEMM_DTYPE_MISMATCH, "A and B value types differ");
+  std::memset(C, 0, sizeof(*C));
+  if ((rc = ensure_device(h))) return rc;
+  return A->dtype == SPGEMM_F32 ? outer_run<float>(h, A, B, acc_capacity, C) : outer_run<double>(h, A, B, acc_capacity, C);
 }
 
 }  // extern "C"

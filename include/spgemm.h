@@ -177,6 +177,19 @@ int spgemm_numeric(spgemm_handle h, spgemm_plan plan, const spgemm_csr* A, const
  * Synchronises twice: inside the symbolic phase, and before the plan's scratch is released. */
 int spgemm(spgemm_handle h, const spgemm_csr* A, const spgemm_csr* B, spgemm_csr* C);
 
+/* Whole product in a pipeline of row blocks (the GPU counterpart of the pipelining / double buffering
+ * of section 5.3: while the workspace of one part of the result is being drained, the next part is
+ * already being prepared): A is cut into nblocks blocks of consecutive rows of about equal numbers of
+ * intermediate products; the symbolic phase of block t + 1 runs on a second stream of the same
+ * priority while the numeric phase of block t runs on the handle's stream, and at most two plans are
+ * alive at a time.  The result comes back as row blocks: C_blocks[t] (host array of nblocks structs,
+ * written) is the CSR matrix of rows block_rows[t] .. block_rows[t+1] - 1 of C (block_rows: host,
+ * nblocks + 1 entries, written), its row pointer starting at 0; stacked, the blocks are exactly the
+ * matrix spgemm() returns.  Buffers come from the handle's allocator (three per block; release with
+ * its free or spgemm_free_device).  Returns when everything is done. */
+int spgemm_pipelined(spgemm_handle h, const spgemm_csr* A, const spgemm_csr* B, int nblocks, spgemm_csr* C_blocks,
+                     int64_t* block_rows);
+
 /* Release a device buffer that spgemm() obtained (routes to the allocator's free). */
 int spgemm_free_device(spgemm_handle h, void* ptr);
 

@@ -29,7 +29,7 @@ STATUS_NAMES = {0: "OK", -1: "INVALID_ARG", -2: "DIM_MISMATCH", -3: "DTYPE_MISMA
 EXPORTED = ("spgemm_create", "spgemm_destroy", "spgemm_set_option", "spgemm_symbolic", "spgemm_numeric", "spgemm",
             "spgemm_free_device", "spgemm_plan_destroy", "spgemm_get_stats", "spgemm_last_error", "spgemm_version",
             "sptensor_unfold_mode3", "spttm_mode3", "sptensor_fold_mode3", "sptensor_unfold", "spttm", "sptensor_fold", "sptensor_unfold_noalloc",
-            "spgemm_dcsr_from_csr", "spgemm_dcsc_from_csr", "spgemm_dcs_free", "spgemm_outer")
+            "spgemm_dcsr_from_csr", "spgemm_dcsc_from_csr", "spgemm_dcs_free", "spgemm_outer", "spgemm_pipelined")
 
 
 class SpgemmError(RuntimeError):
@@ -100,6 +100,7 @@ def load_library():
     lib.spgemm_dcsc_from_csr.argtypes = [C.c_void_p, P(CsrStruct), P(DcsStruct)]
     lib.spgemm_dcs_free.argtypes = [C.c_void_p, P(DcsStruct)]
     lib.spgemm_outer.argtypes = [C.c_void_p, P(DcsStruct), P(DcsStruct), C.c_int64, P(CsrStruct)]
+    lib.spgemm_pipelined.argtypes = [C.c_void_p, P(CsrStruct), P(CsrStruct), C.c_int, P(CsrStruct), P(C.c_int64)]
     lib.spgemm_last_error.argtypes = [C.c_void_p]
     lib.spgemm_last_error.restype = C.c_char_p
     for name in EXPORTED:
@@ -406,3 +407,13 @@ def spgemm_outer(handle: Handle, A: DeviceDCS, B: DeviceDCS, acc_capacity: int =
     sa, sb, sc = A.struct(), B.struct(), CsrStruct()
     handle._check(handle.lib.spgemm_outer(handle.ptr, C.byref(sa), C.byref(sb), int(acc_capacity), C.byref(sc)))
     return _adopt_csr(handle, sc, A.values.dtype, A.ptr.device)
+
+
+def spgemm_pipelined(handle: Handle, A: DeviceCSR, B: DeviceCSR, nblocks: int):
+    """C = A * B as row blocks, symbolic of block t + 1 overlapped with numeric of block t.
+    -> (list of DeviceCSR blocks, list of nblocks + 1 first-row indices)."""
+    sa, sb = A.struct(), B.struct()
+    blocks = (CsrStruct * nblocks)()
+    first = (C.c_int64 * (nblocks + 1))()
+    handle._check(handle.lib.spgemm_pipelined(handle.ptr, C.byref(sa), C.byref(sb), int(nblocks), blocks, first))
+    return [_adopt_csr(handle, blocks[t], A.values.dtype, A.rowptr.device) for t in range(nblocks)], list(first)

@@ -50,7 +50,7 @@ __global__ __launch_bounds__(kCountThreads) void k_count_rows(int64_t m, int64_t
                                                     const int64_t* __restrict__ a_rp, const int32_t* __restrict__ a_col,
                                                     const int64_t* __restrict__ b_rp, int* __restrict__ ip_out,
                                                     unsigned char* __restrict__ bin_out, int* __restrict__ cnt_out,
-                                                    Control* ctl, int force) {
+                                                    Control* ctl, int force, int row_block) {
   __shared__ long long rp[257];
   __shared__ unsigned long long ipl[256];
   __shared__ unsigned hist[kNumBins];
@@ -67,8 +67,9 @@ __global__ __launch_bounds__(kCountThreads) void k_count_rows(int64_t m, int64_t
   if (tid < nr && rp[tid + 1] < rp[tid]) bad = 1;
   if (tid == 0) {
     if (rp[0] < 0 || rp[nr] > nnz_a) bad = 1;
-    if (r0 == 0 && rp[0] != 0) bad = 1;
-    if (r0 + nr == m && rp[nr] != nnz_a) bad = 1;
+    // (a block of rows of a larger matrix keeps that matrix's positions: it neither starts at 0 nor ends at nnz)
+    if (!row_block && r0 == 0 && rp[0] != 0) bad = 1;
+    if (!row_block && r0 + nr == m && rp[nr] != nnz_a) bad = 1;
   }
   __syncthreads();
   if (bad) {

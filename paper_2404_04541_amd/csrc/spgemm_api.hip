@@ -42,6 +42,7 @@ struct spgemm_context {
   int64_t col_list = 1;   // 0 off, 1 automatic size, larger: byte limit
   int block_table = 1;    // 0: never build the block-offset table of B (pieces are bisected)
   int search_ratio = 4;   // searched tiles for rows with at most this many products per entry (0: never)
+  int row_block = 0;      // 1: A is a block of rows of a larger matrix (row pointer values are that matrix's positions)
   std::string err = "";
   bool device_ready = false;
   int num_cus = 0;
@@ -217,7 +218,7 @@ int run_setup(spgemm_context* h, spgemm_plan_s* p, const spgemm_csr* A, const sp
                        B->rows, B->cols, B->nnz, B->rowptr, B->colidx, p->ctl);
     if (m > 0)
       hipLaunchKernelGGL(k_count_rows, dim3((unsigned)ceil_div(m, 256)), dim3(kCountThreads), 0, s, m, A->nnz, B->rows, A->rowptr, A->colidx,
-                         B->rowptr, p->ip, p->bin, p->cnt, p->ctl, h->force);
+                         B->rowptr, p->ip, p->bin, p->cnt, p->ctl, h->force, h->row_block);
   }
   {
     Timer t(h, SPGEMM_K_BIN);
@@ -911,6 +912,128 @@ int sptensor_fold_mode3(spgemm_handle h, int64_t J, const spgemm_csr* Y, int32_t
   hipLaunchKernelGGL(k_tensor_fold, dim3(grid_for(Y->rows, 4, (int64_t)h->num_cus * 32)), dim3(256), 0, h->stream, Y->rows, J, Y->rowptr,
                      (const int32_t*)nullptr, yi, yj, (int32_t*)nullptr);
   HIP_TRY(h, hipGetLastError());
+  return SPGEMM_OK;
+}
+
+// ---- row blocks in a pipeline ------------------------------------------------------------------
+
+int spgemm_pipelined(spgemm_handle h, const spgemm_csr* A, const spgemm_csr* B, int nblocks, spgemm_csr* C_blocks, int64_t* block_rows) {
+  if (!h) return SPGEMM_INVALID_ARG;
+  int rc = check_pair(h, A, B);
+  if (rc) return rc;
+  if (!C_blocks || !block_rows) return fail(h, SPGEMM_INVALID_ARG, "C_blocks and block_rows must not be null");
+  if (nblocks < 1 || nblocks > 4096) return fail(h, SPGEMM_INVALID_ARG, "nblocks takes 1..4096");
+  if ((rc = ensure_device(h))) return rc;
+  const int64_t m = A->rows;
+  for (int t = 0; t < nblocks; ++t) std::memset(&C_blocks[t], 0, sizeof(spgemm_csr));
+  // 1. products per row of the whole A (the count kernel), their prefix on the host, block boundaries of equal work
+  std::vector<int> ip_host((size_t)m);
+  {
+    size_t off = 0;
+    const size_t o_ctl = off; off = align_up(off + sizeof(Control));
+    const size_t o_ip = off; off = align_up(off + (size_t)m * 4);
+    const size_t o_cnt = off; off = align_up(off + (size_t)m * 4);
+    const size_t o_bin = off; off = align_up(off + (size_t)m);
+    unsigned char* tmp = static_cast<unsigned char*>(dev_alloc(h, off));
+    if (!tmp) return fail(h, SPGEMM_ALLOC_FAILED, "allocation for the row-block planning failed");
+    Control* ctl = reinterpret_cast<Control*>(tmp + o_ctl);
+    Control host{};
+    hipLaunchKernelGGL(k_init_control, dim3(1), dim3(64), 0, h->stream, ctl);
+    if (m > 0)
+      hipLaunchKernelGGL(k_count_rows, dim3((unsigned)ceil_div(m, 256)), dim3(kCountThreads), 0, h->stream, m, A->nnz, B->rows, A->rowptr, A->colidx,
+                         B->rowptr, reinterpret_cast<int*>(tmp + o_ip), tmp + o_bin, reinterpret_cast<int*>(tmp + o_cnt), ctl, 0, 0);
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess && m > 0) e = hipMemcpyAsync(ip_host.data(), tmp + o_ip, (size_t)m * 4, hipMemcpyDeviceToHost, h->stream);
+    if (e == hipSuccess) e = hipMemcpyAsync(&host, ctl, sizeof(Control), hipMemcpyDeviceToHost, h->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(h->stream);
+    dev_free(h, tmp);
+    if (e != hipSuccess) return fail(h, SPGEMM_HIP_ERROR, std::string("row-block planning: ") + hipGetErrorString(e));
+    if (host.error) return fail(h, SPGEMM_INVALID_INPUT, "device-side input check failed (column out of range or rowptr not monotone)");
+  }
+  {
+    double total = 0;
+    for (int64_t i = 0; i < m; ++i) total += ip_host[(size_t)i] + 1.0;   // (+1: rows without products still cost a little)
+    double run = 0;
+    int t = 1;
+    block_rows[0] = 0;
+    for (int64_t i = 0; i < m && t < nblocks; ++i) {
+      run += ip_host[(size_t)i] + 1.0;
+      while (t < nblocks && run >= total * t / nblocks) block_rows[t++] = i + 1;
+    }
+    while (t <= nblocks) block_rows[t++] = m;
+    block_rows[nblocks] = m;
+  }
+  // 2. a second context on a stream of its own (same priority) for the symbolic phases
+  hipStream_t s2 = nullptr;
+  HIP_TRY(h, hipStreamCreateWithFlags(&s2, hipStreamNonBlocking));
+  spgemm_context h2 = *h;
+  h2.stream = s2;
+  h2.row_block = 1;
+  h2.timing = 0;
+  h2.timed.clear();
+  h2.event_pool.clear();
+  h2.err.clear();
+  struct Block { spgemm_plan plan = nullptr; int64_t* rp = nullptr; int32_t* col = nullptr; void* val = nullptr; int64_t nnz = 0; hipEvent_t done = nullptr; };
+  std::vector<Block> blk((size_t)nblocks);
+  const size_t vsz = A->dtype == SPGEMM_F32 ? 4 : 8;
+  auto block_of_a = [&](int t) {
+    spgemm_csr a = *A;
+    a.rows = block_rows[t + 1] - block_rows[t];
+    a.rowptr = A->rowptr + block_rows[t];
+    return a;
+  };
+  auto symbolic_of = [&](int t) -> int {
+    const spgemm_csr a = block_of_a(t);
+    blk[(size_t)t].rp = static_cast<int64_t*>(dev_alloc(h, (size_t)(a.rows + 1) * 8));
+    if (!blk[(size_t)t].rp) return fail(h, SPGEMM_ALLOC_FAILED, "allocation of a block's row pointer failed");
+    const int r = spgemm_symbolic(&h2, &a, B, blk[(size_t)t].rp, &blk[(size_t)t].nnz, &blk[(size_t)t].plan);
+    if (r != SPGEMM_OK) h->err = h2.err;
+    return r;
+  };
+  auto release_plan = [&](int t) {
+    Block& b = blk[(size_t)t];
+    if (b.done) { (void)hipEventSynchronize(b.done); (void)hipEventDestroy(b.done); b.done = nullptr; }
+    if (b.plan) { spgemm_plan_destroy(b.plan); b.plan = nullptr; }
+  };
+  rc = symbolic_of(0);
+  for (int t = 0; t < nblocks && rc == SPGEMM_OK; ++t) {
+    Block& b = blk[(size_t)t];
+    const spgemm_csr a = block_of_a(t);
+    // numeric of block t on the handle's stream (enqueued only) ...
+    if (b.nnz > 0) {
+      b.col = static_cast<int32_t*>(dev_alloc(h, (size_t)b.nnz * 4));
+      b.val = dev_alloc(h, (size_t)b.nnz * vsz);
+      if (!b.col || !b.val) { rc = fail(h, SPGEMM_ALLOC_FAILED, "allocation of a block of C failed"); break; }
+      rc = A->dtype == SPGEMM_F32 ? run_numeric<float>(h, b.plan, &a, B, b.rp, b.col, b.val) : run_numeric<double>(h, b.plan, &a, B, b.rp, b.col, b.val);
+      if (rc != SPGEMM_OK) break;
+    }
+    if (hipEventCreateWithFlags(&b.done, hipEventDisableTiming) != hipSuccess || hipEventRecord(b.done, h->stream) != hipSuccess) {
+      rc = fail(h, SPGEMM_HIP_ERROR, "event for a block's numeric phase failed");
+      break;
+    }
+    // ... while the symbolic phase of block t + 1 runs on the other stream (this call returns when it is done)
+    if (t + 1 < nblocks) rc = symbolic_of(t + 1);
+    if (t >= 1) release_plan(t - 1);   // (its numeric phase has been running for a whole symbolic phase: wait and release)
+  }
+  if (hipStreamSynchronize(h->stream) != hipSuccess && rc == SPGEMM_OK) rc = fail(h, SPGEMM_HIP_ERROR, "numeric phase failed");
+  (void)hipStreamSynchronize(s2);
+  for (int t = 0; t < nblocks; ++t) release_plan(t);
+  for (auto e : h2.event_pool) (void)hipEventDestroy(e);
+  (void)hipStreamDestroy(s2);
+  for (auto& tl : h->timed) { h->event_pool.push_back(tl.start); h->event_pool.push_back(tl.stop); }   // (per-block times are not reported)
+  h->timed.clear();
+  if (rc != SPGEMM_OK) {
+    for (auto& b : blk) { dev_free(h, b.rp); dev_free(h, b.col); dev_free(h, b.val); }
+    return rc;
+  }
+  for (int t = 0; t < nblocks; ++t) {
+    const Block& b = blk[(size_t)t];
+    C_blocks[t].rows = block_rows[t + 1] - block_rows[t];
+    C_blocks[t].cols = B->cols;
+    C_blocks[t].nnz = b.nnz;
+    C_blocks[t].dtype = A->dtype;
+    C_blocks[t].rowptr = b.rp; C_blocks[t].colidx = b.col; C_blocks[t].values = b.val;
+  }
   return SPGEMM_OK;
 }
 

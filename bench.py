@@ -9,7 +9,10 @@ Prints one JSON line:
   value      GFLOP/s, counting 2 flops per intermediate product
   roofline   the numeric dense-workspace kernel (the dominant one) against the 8 TB/s HBM peak,
              from algorithmic bytes and HIP-event durations taken inside the timed region
-  cpu_baseline  the CPU checker (std::map Gustavson, all host cores) on a sample of rows
+  roofline_other  the same for the symbolic dense kernel
+  other_configs   ms per pass, GFLOP/s and stream-model fraction of the stencil, rectangular and tensor
+                  configurations (same protocol, fewer steps; not part of `value`)
+  cpu_baseline  the CPU checker (std::map Gustavson, all host cores) on a product-weighted sample of rows
 """
 from __future__ import annotations
 
@@ -26,7 +29,7 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "k_num_dense_rmat20_hbm_traffic.txt")
-KERNEL_SOURCES = ("common.cuh", "dense_kernels.cuh")   # what k_num_dense is compiled from
+KERNEL_SOURCES = ("common.cuh", "dense_kernels.cuh")   # what the dense kernels are compiled from
 
 
 def kernel_source_hash() -> str:
@@ -38,36 +41,68 @@ def kernel_source_hash() -> str:
     return hsh.hexdigest()
 
 
-def measured_traffic():
-    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter summary;
-    None when there is none or when the kernel's sources have changed since it was taken."""
+def measured_traffic(key: str = "hbm_bytes_per_launch"):
+    """HBM bytes per launch of a dense kernel from the committed rocprofv3 counter summary (FETCH_SIZE and WRITE_SIZE,
+    each scaled by what the same counter reads for a plain 1 GiB copy; for kernels with many narrow requests the
+    FETCH_SIZE scale is an upper bound); None when there is none or the kernels' sources changed since it was taken."""
     try:
         fields = dict(line.split(":", 1) for line in open(TRAFFIC_FILE) if ":" in line and not line.startswith("#"))
         if fields["source_sha256"].strip() != kernel_source_hash():
             return None
-        return float(fields["hbm_bytes_per_launch"])
+        return float(fields[key])
     except (OSError, KeyError, ValueError):
         return None
 
 
 def cpu_baseline(A, B, ip_rows: np.ndarray, budget_ip: float = 2.0e8) -> dict:
-    """Time the CPU checker on seeded random non-empty rows holding about budget_ip products."""
+    """Time the CPU checker on rows drawn with probability proportional to their product counts (so that long
+    rows, whose maps are large, weigh as they do in the whole product), about budget_ip products in all."""
     import oracle
     from paper_2404_04541_amd import workloads as W
-    rows = np.nonzero(ip_rows > 0)[0]
-    pick = np.unique(rows[W.rand_below(0, 900, np.arange(8192, dtype=np.uint64), rows.size)])
-    order = np.argsort(W.rand_u64(0, 901, pick.astype(np.uint64)), kind="stable")
-    pick = pick[order]
+    prefix = np.cumsum(ip_rows.astype(np.float64))
+    u = W.rand_unit(0, 900, np.arange(4096, dtype=np.uint64)) * prefix[-1]
+    draw = np.searchsorted(prefix, u, side="right")
+    pick = draw[np.sort(np.unique(draw, return_index=True)[1])]
     n = int(np.searchsorted(np.cumsum(ip_rows[pick]), budget_ip)) + 1
-    pick = np.ascontiguousarray(pick[:n])
+    pick = np.ascontiguousarray(np.sort(pick[:n]))
     oracle.build()
     t0 = time.perf_counter()
     r = oracle.spgemm_rows(A.rowptr, A.colidx, A.values, B.rowptr, B.colidx, B.values, rows=pick)
     dt = time.perf_counter() - t0
     ip = int(r.ip.sum())
     return {"value": 2.0 * ip / dt / 1e9, "unit": "GFLOP/s", "cores": oracle.max_threads(), "kind": "oracle",
-            "sample": f"{pick.size} seeded random non-empty rows of the same A*A ({ip} intermediate products, "
-                      f"{int(r.cnt.sum())} output entries), {dt:.1f} s wall"}
+            "sample": f"{pick.size} rows of the same A*A drawn with probability proportional to their products ({ip} intermediate "
+                      f"products, {int(r.cnt.sum())} output entries), {dt:.1f} s wall"}
+
+
+def stream_bytes(ip_total, nnz_c, nnz_a, m, v):
+    return ip_total * (8 + v) + nnz_c * (4 + v) + nnz_a * (60 + v) + m * 60
+
+
+def time_config(sg, torch, A, B, steps, warmup):
+    """ms per pass (symbolic + numeric, outputs preallocated) of one configuration, and its sizes."""
+    h = sg.Handle()
+    dA = sg.to_device(A)
+    dB = dA if B is A else sg.to_device(B)
+    rp = torch.empty(A.rows + 1, dtype=torch.int64, device="cuda")
+    _, nnz_c, plan = sg.spgemm_symbolic(h, dA, dB, rp)
+    col = torch.empty(nnz_c, dtype=torch.int32, device="cuda")
+    val = torch.empty(nnz_c, dtype=dA.values.dtype, device="cuda")
+    ip_total = plan.stats()["ip_total"]
+    plan.destroy()
+    for it in range(warmup + steps):
+        if it == warmup:
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+        _, n, pl = sg.spgemm_symbolic(h, dA, dB, rp)
+        sg.spgemm_numeric(h, pl, dA, dB, rp, col, val)
+        torch.cuda.synchronize()
+        pl.destroy()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    v = A.values.dtype.itemsize
+    b = stream_bytes(ip_total, nnz_c, A.nnz, A.rows, v)
+    return {"ms_per_step": ms, "GFLOP/s": 2.0 * ip_total / ms / 1e6, "intermediate_products": ip_total, "nnz_c": nnz_c,
+            "effective_hbm_frac": b / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "dtype": "f32" if v == 4 else "f64"}
 
 
 def main() -> int:
@@ -77,6 +112,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--scale", type=int, default=20, help="R-MAT scale (20 = the benchmark configuration)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-configs", action="store_true", help="skip the stencil / rectangular / tensor configurations")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (read 1 GiB, write 1 GiB): the reference for HBM counters")
     args = ap.parse_args()
@@ -138,7 +174,7 @@ def main() -> int:
 
     v = A.values.dtype.itemsize
     m, nnz_a = A.rows, A.nnz
-    bytes_stream = ip_total * (8 + v) + nnz_c * (4 + v) + nnz_a * (60 + v) + m * 60
+    bytes_stream = stream_bytes(ip_total, nnz_c, nnz_a, m, v)
     eff_gbs = bytes_stream * args.steps / dt / 1e9
     # dominant kernel: numeric dense workspace.  Algorithmic bytes per launch = the gathered B
     # entries of its rows (column + value per intermediate product) + the C entries it writes.
@@ -147,6 +183,12 @@ def main() -> int:
     dense_bytes = dense_ip * (4 + v) + dense_nnz * (4 + v)
     dense_ms = per_kernel.get("num_dense", 0.0) / args.steps
     achieved = dense_bytes / (dense_ms * 1e-3) / 1e9 if dense_ms > 0 else 0.0
+    # symbolic dense kernel: the gathered B columns of its rows (4 B per product); what it leaves in the plan
+    # for the numeric phase is extra, not counted
+    sym_ip = sum(st["sym_bin_ip"][4:7])
+    sym_bytes = sym_ip * 4
+    sym_ms = per_kernel.get("sym_dense", 0.0) / args.steps
+    sym_achieved = sym_bytes / (sym_ms * 1e-3) / 1e9 if sym_ms > 0 else 0.0
     out = {
         "metric": "SpGEMM GFLOP/s (2 x intermediate products / s)", "value": gflops, "unit": "GFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
@@ -161,7 +203,22 @@ def main() -> int:
         "roofline": {"kernel": "k_num_dense<float>", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(),
                      "bytes_per_launch": dense_bytes, "ms_per_launch": dense_ms},
+        "roofline_other": [{"kernel": "k_sym_dense", "bound": "hbm", "achieved": sym_achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                            "frac": sym_achieved / HBM_PEAK_GBS, "traffic": measured_traffic("k_sym_dense_hbm_bytes_per_launch"),
+                            "bytes_per_launch": sym_bytes, "ms_per_launch": sym_ms}],
+        "plan_bytes": st["plan_bytes"], "plan_list_bytes_used": st["plan_list_used"],
     }
+    del col, val, rp, dA, dB
+    if not args.no_other_configs:
+        torch.cuda.empty_cache()
+        other = {}
+        for name, make in (("config2 stencil 128^3 A*A f64", W.config2), ("config4 rectangular A*B f64", W.config4),
+                           ("config5 tensor mode-3 unfolding * M f64", W.config5)):
+            A2, B2 = make()
+            other[name] = time_config(sg, torch, A2, B2, steps=5, warmup=2)
+            del A2, B2
+            torch.cuda.empty_cache()
+        out["other_configs"] = other
     if not args.no_cpu_baseline:
         run = np.concatenate([[0], np.cumsum(np.diff(B.rowptr)[A.colidx])])
         ip_rows = run[A.rowptr[1:]] - run[A.rowptr[:-1]]

@@ -7,6 +7,7 @@ import subprocess
 _HERE = os.path.dirname(os.path.abspath(__file__))
 SRC = os.path.join(_HERE, "csrc", "spgemm_api.hip")
 LIB = os.path.join(_HERE, "libspgemm_gfx950.so")
+LIB_CLOCKS = os.path.join(_HERE, "libspgemm_gfx950_clocks.so")   # the same sources with -DSPG_PHASE_CLOCKS (profiling only)
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-munsafe-fp-atomics",
@@ -15,9 +16,11 @@ FLAGS = [
 ]
 
 
-def build_library(verbose: bool = False) -> str:
-    """Compile csrc/ for gfx950 with hipcc (cross-compiles without a GPU)."""
-    cmd = ["hipcc", *FLAGS, "-o", LIB, SRC]
+def build_library(verbose: bool = False, phase_clocks: bool = False) -> str:
+    """Compile csrc/ for gfx950 with hipcc (cross-compiles without a GPU).  phase_clocks: the profiling
+    variant whose dense kernels read the shader clock at phase boundaries (used by phase_profile.py only)."""
+    out_path = LIB_CLOCKS if phase_clocks else LIB
+    cmd = ["hipcc", *FLAGS, *(["-DSPG_PHASE_CLOCKS=1"] if phase_clocks else []), "-o", out_path, SRC]
     if verbose:
         print(" ".join(cmd))
     r = subprocess.run(cmd, capture_output=True, text=True)
@@ -26,8 +29,9 @@ def build_library(verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed:\n" + out)
     if verbose and out.strip():
         print(out)
-    return LIB
+    return out_path
 
 
 if __name__ == "__main__":
     print(build_library(verbose=True))
+    print(build_library(verbose=True, phase_clocks=True))

@@ -29,7 +29,7 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "k_num_dense_rmat20_hbm_traffic.txt")
-KERNEL_SOURCES = ("common.cuh", "dense_kernels.cuh")   # what the dense kernels are compiled from
+KERNEL_SOURCES = ("common.hpp", "dense_kernels.hpp")   # what the dense kernels are compiled from
 
 
 def kernel_source_hash() -> str:

@@ -167,7 +167,10 @@ int spgemm_symbolic(spgemm_handle h, const spgemm_csr* A, const spgemm_csr* B,
  *                       (may be null when nnz_c == 0).
  * Only enqueues work (no synchronisation).  A plan may be
  * reused for further numeric calls with new values on the same structures.
- * Sums are accumulated in double for both value types and rounded once on output. */
+ * Sums are accumulated in double for both value types and rounded once on output (one exception: the
+ * staged coordinate list, taken on request only, stages each float product rounded to float).
+ * The plan's scratch is read by the enqueued kernels: spgemm_plan_destroy waits for the stream when a
+ * numeric phase is still in flight. */
 int spgemm_numeric(spgemm_handle h, spgemm_plan plan, const spgemm_csr* A, const spgemm_csr* B,
                    const int64_t* c_rowptr, int32_t* c_colidx, void* c_values);
 
@@ -193,6 +196,8 @@ int spgemm_pipelined(spgemm_handle h, const spgemm_csr* A, const spgemm_csr* B, 
 /* Release a device buffer that spgemm() obtained (routes to the allocator's free). */
 int spgemm_free_device(spgemm_handle h, void* ptr);
 
+/* Releases the plan's device memory (waits for the stream first when numeric work on the plan may still be
+ * running).  A plan refers to its handle: destroy plans before spgemm_destroy of the handle they came from. */
 int spgemm_plan_destroy(spgemm_plan plan);
 
 /* Statistics of the plan's last symbolic and numeric runs (host struct, written).  With

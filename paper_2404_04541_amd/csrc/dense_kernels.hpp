@@ -22,7 +22,7 @@
 //   The piece of B row k that falls into a tile is found with two loads from a table of
 //   per-row block offsets (ascending B rows), so a pass touches only its own products.
 #pragma once
-#include "common.cuh"
+#include "common.hpp"
 
 namespace spg {
 
@@ -466,6 +466,7 @@ __global__ __launch_bounds__(kDenseThreads) void k_sym_dense(const int* __restri
         if (nt > 0) { tb = atomicAdd(&ctl->tile_cursor, (unsigned)nt); rb = atomicAdd(&ctl->run_cursor, (unsigned)nr); }
         if (last_span) nx = atomicAdd(&ctl->work[0], 1u);
         const bool listed = want_list && at + need <= list_cap;
+        if (want_list && !listed) atomicAdd(&ctl->list_cursor, 0ULL - need);   // (no room: the share goes back, later rows may still fit)
         tp->list_base = listed ? (long long)at : -1;
         tp->list_words = listed && as_words ? fwords : 0;
         tp->tile_base = tb;

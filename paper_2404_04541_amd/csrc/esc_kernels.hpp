@@ -4,7 +4,7 @@
 // expand / sort / reduce-by-key policy of the paper's table of library algorithms
 // (section 4.4) run at wavefront level, one row per GROUP lanes.
 #pragma once
-#include "common.cuh"
+#include "common.hpp"
 
 namespace spg {
 

@@ -7,7 +7,7 @@
 //           the occupied slots come first in ascending column order (hash retrieval),
 //           and that prefix is copied to the row of C.
 #pragma once
-#include "common.cuh"
+#include "common.hpp"
 
 namespace spg {
 

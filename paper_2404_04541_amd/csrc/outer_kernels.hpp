@@ -12,7 +12,7 @@
 // time, and the merge is a rank computation on both sides followed by one reduction of equal
 // neighbours; the stages and the two arrays are the paper's.
 #pragma once
-#include "common.cuh"
+#include "common.hpp"
 
 namespace spg {
 

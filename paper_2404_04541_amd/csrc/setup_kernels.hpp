@@ -1,6 +1,6 @@
 // Per-row intermediate-product count, input checks, binning and the row-count scan.
 #pragma once
-#include "common.cuh"
+#include "common.hpp"
 
 namespace spg {
 

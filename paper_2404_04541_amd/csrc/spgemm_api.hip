@@ -1,5 +1,5 @@
 // C ABI of the SpGEMM library (see include/spgemm.h): argument checks, plan scratch,
-// kernel launches.  All device work is in the *_kernels.cuh headers beside this file.
+// kernel launches.  All device work is in the *_kernels.hpp headers beside this file.
 #include "../../include/spgemm.h"
 
 #include <hip/hip_runtime.h>
@@ -11,14 +11,14 @@
 #include <string>
 #include <vector>
 
-#include "common.cuh"
-#include "setup_kernels.cuh"
-#include "esc_kernels.cuh"
-#include "hash_kernels.cuh"
-#include "dense_kernels.cuh"
-#include "staged_kernels.cuh"
-#include "tensor_kernels.cuh"
-#include "outer_kernels.cuh"
+#include "common.hpp"
+#include "setup_kernels.hpp"
+#include "esc_kernels.hpp"
+#include "hash_kernels.hpp"
+#include "dense_kernels.hpp"
+#include "staged_kernels.hpp"
+#include "tensor_kernels.hpp"
+#include "outer_kernels.hpp"
 
 using namespace spg;
 
@@ -74,6 +74,7 @@ struct spgemm_plan_s {
   int64_t scan_blocks = 0;
   bool symbolic_done = false;
   bool numeric_pending = false;   // timed numeric launches not yet folded into stats
+  bool numeric_in_flight = false; // numeric kernels were enqueued and the stream has not been waited for since
   spgemm_stats stats{};
 };
 
@@ -192,6 +193,12 @@ void collect_times(spgemm_context* h, spgemm_stats* st) {
     h->event_pool.push_back(t.start);
     h->event_pool.push_back(t.stop);
   }
+  h->timed.clear();
+}
+
+// Forget the launches timed so far (their events go back to the pool).
+void drop_timed(spgemm_context* h) {
+  for (auto& t : h->timed) { h->event_pool.push_back(t.start); h->event_pool.push_back(t.stop); }
   h->timed.clear();
 }
 
@@ -489,6 +496,8 @@ const char* spgemm_last_error(spgemm_handle h) { return h ? h->err.c_str() : "nu
 
 int spgemm_plan_destroy(spgemm_plan p) {
   if (!p) return SPGEMM_INVALID_ARG;
+  // the numeric kernels read the plan's scratch: they must have finished before it is released
+  if (p->numeric_in_flight) (void)hipStreamSynchronize(p->h->stream);
   dev_free(p->h, p->scratch);
   dev_free(p->h, p->scratch2);
   dev_free(p->h, p->scratch3);
@@ -502,6 +511,7 @@ int spgemm_get_stats(spgemm_plan p, spgemm_stats* out) {
   if (p->numeric_pending) {
     spgemm_context* h = p->h;
     if (!h->timed.empty()) HIP_TRY(h, hipEventSynchronize(h->timed.back().stop));
+    p->numeric_in_flight = false;
     for (int c = SPGEMM_K_NUM_ESC; c <= SPGEMM_K_NUM_STAGED; ++c) { p->stats.kernel_ms[c] = 0; p->stats.kernel_launches[c] = 0; }
     collect_times(h, &p->stats);
     p->numeric_pending = false;
@@ -518,6 +528,7 @@ int spgemm_symbolic(spgemm_handle h, const spgemm_csr* A, const spgemm_csr* B, i
   if (!c_rowptr || !nnz_c || !plan) return fail(h, SPGEMM_INVALID_ARG, "c_rowptr, nnz_c and plan must not be null");
   *plan = nullptr;
   if ((rc = ensure_device(h))) return rc;
+  drop_timed(h);   // (timed launches of an earlier plan that nobody asked about)
 
   spgemm_plan_s* p = new (std::nothrow) spgemm_plan_s();
   if (!p) return fail(h, SPGEMM_ALLOC_FAILED, "host allocation failed");
@@ -559,7 +570,7 @@ int spgemm_symbolic(spgemm_handle h, const spgemm_csr* A, const spgemm_csr* B, i
   }
   if (rc != SPGEMM_OK) {
     (void)hipStreamSynchronize(h->stream);
-    h->timed.clear();
+    drop_timed(h);
     spgemm_plan_destroy(p);
     return rc;
   }
@@ -613,6 +624,7 @@ int spgemm_numeric(spgemm_handle h, spgemm_plan p, const spgemm_csr* A, const sp
                                 : run_numeric<double>(h, p, A, B, c_rowptr, c_colidx, c_values);
   if (rc != SPGEMM_OK) return rc;
   p->numeric_pending = h->timing != 0;
+  p->numeric_in_flight = true;
   return SPGEMM_OK;
 }
 
@@ -656,6 +668,19 @@ int spgemm(spgemm_handle h, const spgemm_csr* A, const spgemm_csr* B, spgemm_csr
   if (nnz > 0) {
     col = static_cast<int32_t*>(dev_alloc(h, (size_t)nnz * 4));
     val = dev_alloc(h, (size_t)nnz * vsz);
+    if ((!col || !val) && plan->scratch3 && h->col_list) {
+      // the plan's optional structure list may be what stands in the way: plan again without it
+      dev_free(h, col); dev_free(h, val);
+      spgemm_plan_destroy(plan);
+      plan = nullptr;
+      const int64_t keep = h->col_list;
+      h->col_list = 0;
+      rc = spgemm_symbolic(h, A, B, rp, &nnz, &plan);
+      h->col_list = keep;
+      if (rc != SPGEMM_OK) { dev_free(h, rp); return rc; }
+      col = static_cast<int32_t*>(dev_alloc(h, (size_t)nnz * 4));
+      val = dev_alloc(h, (size_t)nnz * vsz);
+    }
     if (!col || !val) {
       dev_free(h, col); dev_free(h, val); dev_free(h, rp);
       spgemm_plan_destroy(plan);
@@ -1020,8 +1045,7 @@ int spgemm_pipelined(spgemm_handle h, const spgemm_csr* A, const spgemm_csr* B, 
   for (int t = 0; t < nblocks; ++t) release_plan(t);
   for (auto e : h2.event_pool) (void)hipEventDestroy(e);
   (void)hipStreamDestroy(s2);
-  for (auto& tl : h->timed) { h->event_pool.push_back(tl.start); h->event_pool.push_back(tl.stop); }   // (per-block times are not reported)
-  h->timed.clear();
+  drop_timed(h);   // (per-block times are not reported)
   if (rc != SPGEMM_OK) {
     for (auto& b : blk) { dev_free(h, b.rp); dev_free(h, b.col); dev_free(h, b.val); }
     return rc;

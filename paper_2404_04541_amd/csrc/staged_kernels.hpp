@@ -12,8 +12,8 @@
 // After the single pass over global memory all work is LDS-only, so a row costs one global
 // round trip however wide its columns are spread.  B rows need not be sorted.
 #pragma once
-#include "common.cuh"
-#include "dense_kernels.cuh"
+#include "common.hpp"
+#include "dense_kernels.hpp"
 
 namespace spg {
 

@@ -9,7 +9,7 @@
 //            lanes per digit with ballots, which keeps the pass stable
 //   compress row pointer from the sorted keys, columns and permuted values
 #pragma once
-#include "common.cuh"
+#include "common.hpp"
 
 namespace spg {
 

@@ -114,7 +114,9 @@ def test_allocator_that_fails_part_way_leaves_nothing_behind():
             if state["n"] < fail_at:       # the failing call was never reached: the sweep is over
                 n_ok = state["n"]
                 break
-            optional += 1                   # the plan's structure list is optional: the product goes on without it
+            # the plan's structure list is optional (the product goes on without it), and a refused allocation of C
+            # makes the library plan again without that list and ask once more
+            optional += 1
             continue
         # the optional structure list may be refused without failing the product; every other refusal is an error
         assert rc == -5, (fail_at, rc, lib.spgemm_last_error(h))
@@ -129,7 +131,7 @@ def test_allocator_that_fails_part_way_leaves_nothing_behind():
         assert not live
         lib.spgemm_destroy(h)
         calls += 1
-    assert n_ok is not None and calls >= 4 and optional <= 1, "the sweep never reached a run without a failing allocation"
+    assert n_ok is not None and calls >= 3 and optional <= 3, "the sweep never reached a run without a failing allocation"
 
 
 def test_numeric_with_other_operands_than_the_plans():

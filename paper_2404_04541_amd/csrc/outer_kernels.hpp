@@ -37,6 +37,38 @@ __global__ __launch_bounds__(1024) void k_scan_i64(int64_t n, long long* __restr
   if (tid == 1023) v[n] = part[1023];
 }
 
+// Exclusive scan of n 32-bit counters in place, in three steps: sums of tiles of kScanTileU32 counters,
+// a scan of those sums (one workgroup: k_scan_u32), and the scan inside every tile on top of its sum.
+constexpr int kScanTileU32 = 4096;   // 256 threads x 16 counters
+__global__ __launch_bounds__(256) void k_scan_tile_sums(int64_t n, const unsigned* __restrict__ v, unsigned* __restrict__ sums) {
+  __shared__ unsigned ws[4];
+  const int64_t base = (int64_t)blockIdx.x * kScanTileU32;
+  unsigned s = 0;
+  for (int t = 0; t < 16; ++t) {
+    const int64_t i = base + (int64_t)t * 256 + threadIdx.x;
+    if (i < n) s += v[i];
+  }
+  s = (unsigned)wave_sum((int)s);
+  if ((threadIdx.x & 63) == 0) ws[threadIdx.x >> 6] = s;
+  __syncthreads();
+  if (threadIdx.x == 0) sums[blockIdx.x] = ws[0] + ws[1] + ws[2] + ws[3];
+}
+
+__global__ __launch_bounds__(256) void k_scan_tile_final(int64_t n, unsigned* __restrict__ v, const unsigned* __restrict__ sums) {
+  __shared__ unsigned ws[4];
+  const int64_t base = (int64_t)blockIdx.x * kScanTileU32 + (int64_t)threadIdx.x * 16;   // a thread owns 16 consecutive counters
+  unsigned x[16], s = 0;
+#pragma unroll
+  for (int t = 0; t < 16; ++t) { x[t] = base + t < n ? v[base + t] : 0u; s += x[t]; }
+  const unsigned incl = (unsigned)wave_incl_scan((int)s);
+  if ((threadIdx.x & 63) == 63) ws[threadIdx.x >> 6] = incl;
+  __syncthreads();
+  unsigned run = sums[blockIdx.x] + incl - s;
+  for (int w = 0; w < (int)(threadIdx.x >> 6); ++w) run += ws[w];
+#pragma unroll
+  for (int t = 0; t < 16; ++t) { if (base + t < n) v[base + t] = run; run += x[t]; }
+}
+
 // Row index of every entry of a CSR matrix (a wave per row).
 __global__ __launch_bounds__(256) void k_expand_rows(int64_t rows, const int64_t* __restrict__ rowptr, int32_t* __restrict__ out) {
   const int64_t stride = (int64_t)gridDim.x * (blockDim.x / kWave);

@@ -1076,6 +1076,14 @@ __global__ void k_pair_keys(int64_t n, const int32_t* __restrict__ hi, const int
   }
 }
 
+// In-place exclusive scan of n counters (n may be hundreds of millions); sums: ceil(n / kScanTileU32) + 1 slots of scratch.
+void scan_u32_large(spgemm_context* h, int64_t n, unsigned* v, unsigned* sums) {
+  const int64_t tiles = ceil_div(n > 0 ? n : 1, kScanTileU32);
+  hipLaunchKernelGGL(k_scan_tile_sums, dim3((unsigned)tiles), dim3(256), 0, h->stream, n, v, sums);
+  hipLaunchKernelGGL(k_scan_u32, dim3(1), dim3(1024), 0, h->stream, tiles, sums);
+  hipLaunchKernelGGL(k_scan_tile_final, dim3((unsigned)tiles), dim3(256), 0, h->stream, n, v, sums);
+}
+
 struct DevBufs {   // device buffers released together
   spgemm_context* h;
   std::vector<void*> v;
@@ -1103,7 +1111,9 @@ int dcs_compress(spgemm_context* h, int64_t n, int64_t nnz, const int64_t* ptr, 
   const unsigned g = grid_for(n, 256, (int64_t)h->num_cus * 32);
   hipLaunchKernelGGL(k_dcs_flags, dim3(g), dim3(256), 0, s, n, ptr, pos);
   hipLaunchKernelGGL(k_clear_int, dim3(1), dim3(64), 0, s, reinterpret_cast<int*>(pos + n));
-  hipLaunchKernelGGL(k_scan_u32, dim3(1), dim3(1024), 0, s, n + 1, pos);
+  unsigned* sums = bufs.get<unsigned>((size_t)ceil_div(n + 1, kScanTileU32) + 1);
+  if (!sums) return fail(h, SPGEMM_ALLOC_FAILED, "allocation for the doubly compressed format failed");
+  scan_u32_large(h, n + 1, pos, sums);
   unsigned total = 0;
   HIP_TRY(h, hipMemcpyAsync(&total, pos + n, 4, hipMemcpyDeviceToHost, s));
   HIP_TRY(h, hipStreamSynchronize(s));
@@ -1152,10 +1162,11 @@ int outer_run(spgemm_context* h, const spgemm_dcs* A, const spgemm_dcs* B, int64
   auto reduce = [&](int64_t cnt, const unsigned long long* k, const unsigned* sq, const double* v, unsigned long long** ok, double** ov,
                     int64_t* on) -> int {
     unsigned* pos = bufs.get<unsigned>((size_t)cnt + 1);
-    if (!pos) return fail(h, SPGEMM_ALLOC_FAILED, "allocation for the merge stage failed");
+    unsigned* sums = bufs.get<unsigned>((size_t)ceil_div(cnt + 1, kScanTileU32) + 1);
+    if (!pos || !sums) return fail(h, SPGEMM_ALLOC_FAILED, "allocation for the merge stage failed");
     hipLaunchKernelGGL(k_outer_heads, dim3(grid_for(cnt, 256, cap_grid)), dim3(256), 0, s, cnt, k, pos);
     hipLaunchKernelGGL(k_clear_int, dim3(1), dim3(64), 0, s, reinterpret_cast<int*>(pos + cnt));
-    hipLaunchKernelGGL(k_scan_u32, dim3(1), dim3(1024), 0, s, cnt + 1, pos);
+    scan_u32_large(h, cnt + 1, pos, sums);
     unsigned uniq = 0;
     HIP_TRY(h, hipMemcpyAsync(&uniq, pos + cnt, 4, hipMemcpyDeviceToHost, s));
     HIP_TRY(h, hipStreamSynchronize(s));
@@ -1166,6 +1177,7 @@ int outer_run(spgemm_context* h, const spgemm_dcs* A, const spgemm_dcs* B, int64
     HIP_TRY(h, hipGetLastError());
     *on = uniq;
     bufs.release(pos);
+    bufs.release(sums);
     return SPGEMM_OK;
   };
   const int bits_lo = bits_of(n), bits_hi = bits_of(m);

@@ -20,7 +20,7 @@ __global__ __launch_bounds__(256) void k_esc(const int* __restrict__ perm, const
                                               int32_t* __restrict__ c_col, T* __restrict__ c_val) {
   static_assert(CAP == 2 * GROUP, "each lane owns two list positions");
   constexpr int kGroups = 256 / GROUP;
-  __shared__ int s_keys[kGroups][CAP];
+  __shared__ __align__(16) int s_keys[kGroups][CAP];
   __shared__ double s_vals[NUMERIC ? kGroups : 1][NUMERIC ? CAP : 1];
   if (ctl->error) return;
   const unsigned first = ctl->offset[phase][bin];
@@ -77,8 +77,36 @@ __global__ __launch_bounds__(256) void k_esc(const int* __restrict__ perm, const
     // pad the tail so that it sorts behind every real column
     for (int t = filled + gl; t < CAP; t += GROUP) keys[t] = kPadKey;
     group_sync<GROUP>();
-    // ---- sort
-    bitonic_sort_lds<GROUP, CAP, double>(keys, vals, CAP, gl);
+    // ---- sort.  Columns alone go through the bitonic network.  With values, an exchange in the network
+    // would move 12 bytes through LDS per entry and stage; there an entry's place is counted instead:
+    // the number of entries before it (smaller column, or the same column and an earlier position);
+    // every lane counts for its two entries while the group reads the list four keys at a time (one
+    // address for the whole group: no bank conflicts)
+    if constexpr (!NUMERIC) {
+      bitonic_sort_lds<GROUP, CAP, double>(keys, vals, CAP, gl);
+    } else {
+      const int e0 = gl, e1 = gl + GROUP;
+      const unsigned ka = (unsigned)keys[e0], kb = (unsigned)keys[e1];
+      const double va = vals[e0], vb = vals[e1];
+      int nscan = CAP;
+      if constexpr (GROUP == kWave) nscan = __builtin_amdgcn_readfirstlane((filled + 3) & ~3);
+      int ra = 0, rb = 0;
+#pragma unroll 2
+      for (int j = 0; j < nscan; j += 4) {
+        const int4 q4 = *reinterpret_cast<const int4*>(&keys[j]);
+        const unsigned q[4] = {(unsigned)q4.x, (unsigned)q4.y, (unsigned)q4.z, (unsigned)q4.w};
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+          ra += q[x] < ka + (j + x < e0 ? 1u : 0u) ? 1 : 0;
+          rb += q[x] < kb + (j + x < e1 ? 1u : 0u) ? 1 : 0;
+        }
+      }
+      group_sync<GROUP>();
+      // (positions from `filled` on hold padding and stay as they are)
+      if (e0 < filled) { keys[ra] = (int)ka; vals[ra] = va; }
+      if (e1 < filled) { keys[rb] = (int)kb; vals[rb] = vb; }
+      group_sync<GROUP>();
+    }
     // ---- merge: a list position is a head when its column differs from its left neighbour
     const int i0 = 2 * gl, i1 = 2 * gl + 1;
     const int k0 = keys[i0], k1 = keys[i1];

@@ -306,6 +306,8 @@ int run_symbolic(spgemm_context* h, spgemm_plan_s* p, const spgemm_csr* A, const
   hipStream_t s = h->stream;
   const int64_t m = p->m;
   const int64_t cap_small = (int64_t)h->num_cus * 32;
+  // sorted-list keys can carry their list position when every column, shifted by the list's log2 capacity, stays below the padding key
+  const int pack32 = B->cols <= (int64_t(1) << 25) ? 1 : 0, pack128 = B->cols <= (int64_t(1) << 23) ? 1 : 0;
   const size_t lds_hash_small = hash_lds_bytes<64, 10, false>();
   const size_t lds_hash_large = hash_lds_bytes<256, 12, false>();
   const unsigned* hist = host.hist[0];
@@ -332,11 +334,11 @@ int run_symbolic(spgemm_context* h, spgemm_plan_s* p, const spgemm_csr* A, const
       if (hist[0])
         hipLaunchKernelGGL((k_esc<16, 32, T, false>), dim3(grid_for(hist[0], 16, cap_small)), dim3(256), 0, s, p->perm_sym, p->ctl, 0, 0,
                            A->rowptr, A->colidx, (const T*)nullptr, B->rowptr, B->colidx, (const T*)nullptr, p->cnt,
-                           (const int64_t*)nullptr, (int32_t*)nullptr, (T*)nullptr);
+                           (const int64_t*)nullptr, (int32_t*)nullptr, (T*)nullptr, pack32);
       if (hist[1])
         hipLaunchKernelGGL((k_esc<64, 128, T, false>), dim3(grid_for(hist[1], 4, cap_small)), dim3(256), 0, s, p->perm_sym, p->ctl, 0, 1,
                            A->rowptr, A->colidx, (const T*)nullptr, B->rowptr, B->colidx, (const T*)nullptr, p->cnt,
-                           (const int64_t*)nullptr, (int32_t*)nullptr, (T*)nullptr);
+                           (const int64_t*)nullptr, (int32_t*)nullptr, (T*)nullptr, pack128);
     }
     {
       Timer t(h, SPGEMM_K_SYM_HASH);
@@ -388,6 +390,8 @@ int run_numeric(spgemm_context* h, spgemm_plan_s* p, const spgemm_csr* A, const 
   const int64_t m = p->m;
   if (m == 0) return SPGEMM_OK;
   const int64_t cap_small = (int64_t)h->num_cus * 32;
+  // sorted-list keys can carry their list position when every column, shifted by the list's log2 capacity, stays below the padding key
+  const int pack32 = B->cols <= (int64_t(1) << 25) ? 1 : 0, pack128 = B->cols <= (int64_t(1) << 23) ? 1 : 0;
   const T* a_val = static_cast<const T*>(A->values);
   const T* b_val = static_cast<const T*>(B->values);
   T* c_val = static_cast<T*>(c_val_v);
@@ -399,10 +403,10 @@ int run_numeric(spgemm_context* h, spgemm_plan_s* p, const spgemm_csr* A, const 
     Timer t(h, SPGEMM_K_NUM_ESC);
     if (hist[0])
       hipLaunchKernelGGL((k_esc<16, 32, T, true>), dim3(grid_for(hist[0], 16, cap_small)), dim3(256), 0, s, p->perm_num, p->ctl, 1, 0,
-                         A->rowptr, A->colidx, a_val, B->rowptr, B->colidx, b_val, (int*)nullptr, c_rp, c_col, c_val);
+                         A->rowptr, A->colidx, a_val, B->rowptr, B->colidx, b_val, (int*)nullptr, c_rp, c_col, c_val, pack32);
     if (hist[1])
       hipLaunchKernelGGL((k_esc<64, 128, T, true>), dim3(grid_for(hist[1], 4, cap_small)), dim3(256), 0, s, p->perm_num, p->ctl, 1, 1,
-                         A->rowptr, A->colidx, a_val, B->rowptr, B->colidx, b_val, (int*)nullptr, c_rp, c_col, c_val);
+                         A->rowptr, A->colidx, a_val, B->rowptr, B->colidx, b_val, (int*)nullptr, c_rp, c_col, c_val, pack128);
   }
   {
     Timer t(h, SPGEMM_K_NUM_HASH);

@@ -67,6 +67,22 @@ def test_hash_retrieval_with_columns_too_wide_to_pack():
     run(A, W.random_csr(400, 9_000_000, 10, 83), HASH, what="hash, 9M columns")
 
 
+def test_sorted_list_keys_too_wide_to_pack():
+    # beyond 2^25 (short list) and 2^23 (long list) columns a key of the sorted-list workspace cannot
+    # carry its list position; equal columns are then ordered by position while they are counted.
+    # Few distinct columns spread over a wide range: nearly every product has partners to merge with.
+    stretch = 700_001
+    for a_mean, b_mean, seed in ((3, 5, 84), (6, 12, 86)):   # products per row mostly <= 32, resp. mostly 33..128
+        A = W.random_csr(600, 400, a_mean, seed)
+        B0 = W.random_csr(400, 60, b_mean, seed + 1)
+        B = W.CSR(400, 60 * stretch, B0.rowptr, (B0.colidx.astype(np.int64) * stretch).astype(np.int32), B0.values)
+        for force in (AUTO, LIST):
+            st = run(A, B, force, what=f"wide sorted-list keys, means {a_mean}/{b_mean}, force={force}")
+            assert st["num_bin_rows"][0] + st["num_bin_rows"][1] > 300
+        # the same structure with narrow columns takes the packed route
+        run(A, B0, LIST, what="narrow sorted-list keys")
+
+
 def test_stencil_small_grid():
     a, b = W.config2(g=12)
     st = run(a, b, what="stencil 12^3")

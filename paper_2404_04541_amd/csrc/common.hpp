@@ -72,6 +72,15 @@ __device__ __forceinline__ void clk_flush(ClkLds* c, unsigned long long* out) {
 #define SPG_CLK(...)
 #endif
 
+// A few consecutive elements behind a pointer that is only element-aligned, fetched by one load
+// instruction: a gather costs the memory pipeline one pass per cache line and instruction, so a lane
+// that wants neighbouring elements should ask for them together.
+template <typename E, int N>
+struct __attribute__((packed, aligned(sizeof(E)))) Run { E v[N]; };
+
+template <typename E, int N>
+__device__ __forceinline__ Run<E, N> load_run(const E* p) { return *reinterpret_cast<const Run<E, N>*>(p); }
+
 __device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
 
 __device__ __forceinline__ void wave_sync() {

@@ -132,8 +132,9 @@ __device__ __forceinline__ void stream_columns(int64_t a0, int d, const int32_t*
     int len = 0;
     if (e < d) {
       const int k = a_col[a0 + e];
-      s = b_rp[k];
-      int64_t en = b_rp[k + 1];
+      const Run<int64_t, 2> bounds = load_run<int64_t, 2>(b_rp + k);
+      s = bounds.v[0];
+      int64_t en = bounds.v[1];
       range(k, s, en);
       len = (int)(en - s);
     }
@@ -208,7 +209,8 @@ __global__ __launch_bounds__(256) void k_block_ptrs(int64_t rows, int nb1, const
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
     const int64_t k = i / nb1;
     const int b = (int)(i - k * nb1);
-    const int64_t s = b_rp[k], en = b_rp[k + 1];
+    const Run<int64_t, 2> bounds = load_run<int64_t, 2>(b_rp + k);
+    const int64_t s = bounds.v[0], en = bounds.v[1];
     const int len = (int)(en - s);
     if (len <= kWalkLen) {
       if (b != 0) continue;

@@ -35,7 +35,7 @@ __global__ __launch_bounds__(256) void k_esc(const int* __restrict__ perm, const
                                               const T* __restrict__ a_val, const int64_t* __restrict__ b_rp,
                                               const int32_t* __restrict__ b_col, const T* __restrict__ b_val,
                                               int* __restrict__ cnt, const int64_t* __restrict__ c_rp,
-                                              int32_t* __restrict__ c_col, T* __restrict__ c_val, int pack) {
+                                              int32_t* __restrict__ c_col, T* __restrict__ c_val, int pack, int64_t b_nnz) {
   static_assert(CAP == 2 * GROUP, "each lane owns two list positions");
   constexpr int kGroups = 256 / GROUP;
   constexpr int kLogCap = CAP == 32 ? 5 : 7;
@@ -72,8 +72,9 @@ __global__ __launch_bounds__(256) void k_esc(const int* __restrict__ perm, const
       int64_t bs = 0; int len = 0; double av = 0.0;
       if (e < d) {
         const int k = a_col[a0 + e];
-        bs = b_rp[k];
-        len = (int)(b_rp[k + 1] - bs);
+        const Run<int64_t, 2> bounds = load_run<int64_t, 2>(b_rp + k);
+        bs = bounds.v[0];
+        len = (int)(bounds.v[1] - bs);
         if (NUMERIC) av = (double)a_val[a0 + e];
       }
       const int incl = group_incl_scan<GROUP>(len);
@@ -117,11 +118,22 @@ __global__ __launch_bounds__(256) void k_esc(const int* __restrict__ perm, const
       for (int t0 = 0; t0 < len; t0 += 4) {   // four loads in flight per lane
         int cc[4];
         T vv[4];
+        if (bs + t0 + 4 <= b_nnz) {   // four elements exist behind the position, whatever the row's length
+          const Run<int32_t, 4> qc = load_run<int32_t, 4>(b_col + bs + t0);
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          const bool ok = t0 + u < len;
-          cc[u] = ok ? b_col[bs + t0 + u] : 0;
-          if (NUMERIC) vv[u] = ok ? b_val[bs + t0 + u] : T(0);
+          for (int u = 0; u < 4; ++u) cc[u] = qc.v[u];
+          if (NUMERIC) {
+            const Run<T, 4> qv = load_run<T, 4>(b_val + bs + t0);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) vv[u] = qv.v[u];
+          }
+        } else {
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            const bool ok = t0 + u < len;
+            cc[u] = ok ? b_col[bs + t0 + u] : 0;
+            if (NUMERIC) vv[u] = ok ? b_val[bs + t0 + u] : T(0);
+          }
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {

@@ -113,8 +113,9 @@ __global__ __launch_bounds__(256) void k_hash(const int* __restrict__ perm, cons
         double av = 0.0;
         if (e < d) {
           const int k = a_col[a0 + e];
-          bs = b_rp[k];
-          len = (int)(b_rp[k + 1] - bs);
+          const Run<int64_t, 2> bounds = load_run<int64_t, 2>(b_rp + k);
+          bs = bounds.v[0];
+          len = (int)(bounds.v[1] - bs);
           if (NUMERIC) av = (double)a_val[a0 + e];
         }
         int total;

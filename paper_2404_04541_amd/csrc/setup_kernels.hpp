@@ -93,7 +93,8 @@ __global__ __launch_bounds__(kCountThreads) void k_count_rows(int64_t m, int64_t
       len[u] = 0;
       if (p < hi) {
         if (k[u] < 0 || k[u] >= b_rows) { badcol = true; continue; }
-        len[u] = b_rp[k[u] + 1] - b_rp[k[u]];
+        const Run<int64_t, 2> bounds = load_run<int64_t, 2>(b_rp + k[u]);   // (both ends of the row in one load)
+        len[u] = bounds.v[1] - bounds.v[0];
         if (len[u] < 0) { badcol = true; len[u] = 0; }
       }
     }

@@ -334,11 +334,11 @@ int run_symbolic(spgemm_context* h, spgemm_plan_s* p, const spgemm_csr* A, const
       if (hist[0])
         hipLaunchKernelGGL((k_esc<16, 32, T, false>), dim3(grid_for(hist[0], 16, cap_small)), dim3(256), 0, s, p->perm_sym, p->ctl, 0, 0,
                            A->rowptr, A->colidx, (const T*)nullptr, B->rowptr, B->colidx, (const T*)nullptr, p->cnt,
-                           (const int64_t*)nullptr, (int32_t*)nullptr, (T*)nullptr, pack32);
+                           (const int64_t*)nullptr, (int32_t*)nullptr, (T*)nullptr, pack32, B->nnz);
       if (hist[1])
         hipLaunchKernelGGL((k_esc<64, 128, T, false>), dim3(grid_for(hist[1], 4, cap_small)), dim3(256), 0, s, p->perm_sym, p->ctl, 0, 1,
                            A->rowptr, A->colidx, (const T*)nullptr, B->rowptr, B->colidx, (const T*)nullptr, p->cnt,
-                           (const int64_t*)nullptr, (int32_t*)nullptr, (T*)nullptr, pack128);
+                           (const int64_t*)nullptr, (int32_t*)nullptr, (T*)nullptr, pack128, B->nnz);
     }
     {
       Timer t(h, SPGEMM_K_SYM_HASH);
@@ -403,10 +403,10 @@ int run_numeric(spgemm_context* h, spgemm_plan_s* p, const spgemm_csr* A, const 
     Timer t(h, SPGEMM_K_NUM_ESC);
     if (hist[0])
       hipLaunchKernelGGL((k_esc<16, 32, T, true>), dim3(grid_for(hist[0], 16, cap_small)), dim3(256), 0, s, p->perm_num, p->ctl, 1, 0,
-                         A->rowptr, A->colidx, a_val, B->rowptr, B->colidx, b_val, (int*)nullptr, c_rp, c_col, c_val, pack32);
+                         A->rowptr, A->colidx, a_val, B->rowptr, B->colidx, b_val, (int*)nullptr, c_rp, c_col, c_val, pack32, B->nnz);
     if (hist[1])
       hipLaunchKernelGGL((k_esc<64, 128, T, true>), dim3(grid_for(hist[1], 4, cap_small)), dim3(256), 0, s, p->perm_num, p->ctl, 1, 1,
-                         A->rowptr, A->colidx, a_val, B->rowptr, B->colidx, b_val, (int*)nullptr, c_rp, c_col, c_val, pack128);
+                         A->rowptr, A->colidx, a_val, B->rowptr, B->colidx, b_val, (int*)nullptr, c_rp, c_col, c_val, pack128, B->nnz);
   }
   {
     Timer t(h, SPGEMM_K_NUM_HASH);

@@ -112,8 +112,9 @@ __global__ __launch_bounds__(kDenseThreads) void k_num_staged(const int* __restr
       if (e < d) {
         const int k = a_col[a0 + e];
         av = a_val[a0 + e];
-        s = b_rp[k];
-        len = (int)(b_rp[k + 1] - s);
+        const Run<int64_t, 2> bounds = load_run<int64_t, 2>(b_rp + k);
+        s = bounds.v[0];
+        len = (int)(bounds.v[1] - s);
       }
       int idx, cpre, epre, np, nchunks, nel;
       block_excl_scan3(len > 0 ? 1 : 0, (len + kWave - 1) >> 6, len, idx, cpre, epre, np, nchunks, nel, red);

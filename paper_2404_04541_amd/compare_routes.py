@@ -39,7 +39,7 @@ def main() -> int:
             Ac, Br = sg.dcsc_from_csr(h, dA), sg.dcsr_from_csr(h, dB)
             t_outer = timed(lambda: sg.spgemm_outer(h, Ac, Br), torch)
             C = sg.spgemm_outer(h, Ac, Br)
-            print(f"{name}: row-wise spgemm {t_row:.2f}; outer product {t_outer:.2f} (+ {t_conv:.2f} to build the doubly compressed operands); "
+            print(f"{name}: row-wise spgemm {t_row:.2f} ms; outer product {t_outer:.2f} ms (+ {t_conv:.2f} ms to build the doubly compressed operands); "
                   f"nnz(C) {C.nnz}")
     else:
         A, _ = W.config3(args.scale)

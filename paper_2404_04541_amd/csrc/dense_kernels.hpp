@@ -197,9 +197,8 @@ __device__ __forceinline__ void stream_columns(int64_t a0, int d, const int32_t*
 }
 
 // For ascending B rows: bp[k * nb1 + b] = number of entries of row k with a column below
-// b * kBlkCols (b = nb1 - 1 gives the row length).  One thread per table slot: rows of at
-// most kWalkLen entries are walked once by the thread of slot 0, longer rows are bisected.
-constexpr int kWalkLen = 32;
+// b * kBlkCols (b = nb1 - 1 gives the row length).  One thread per table slot, each bisecting its
+// row (the threads of a row read the same few lines, and the table leaves in coalesced stores).
 __global__ __launch_bounds__(256) void k_block_ptrs(int64_t rows, int nb1, const int64_t* __restrict__ b_rp,
                                                     const int32_t* __restrict__ b_col, const Control* __restrict__ ctl,
                                                     int* __restrict__ bp) {
@@ -211,23 +210,11 @@ __global__ __launch_bounds__(256) void k_block_ptrs(int64_t rows, int nb1, const
     const int b = (int)(i - k * nb1);
     const Run<int64_t, 2> bounds = load_run<int64_t, 2>(b_rp + k);
     const int64_t s = bounds.v[0], en = bounds.v[1];
-    const int len = (int)(en - s);
-    if (len <= kWalkLen) {
-      if (b != 0) continue;
-      int* row = bp + k * nb1;
-      int nextb = 0;
-      for (int t = 0; t < len; ++t) {
-        const int cb = b_col[s + t] >> kBlkShift;
-        for (; nextb <= cb; ++nextb) row[nextb] = t;
-      }
-      for (; nextb < nb1; ++nextb) row[nextb] = len;
-    } else {
-      int off;
-      if (b == 0) off = 0;
-      else if (b == nb1 - 1) off = len;
-      else off = (int)(lower_bound_i32(b_col, s, en, b << kBlkShift) - s);
-      bp[i] = off;
-    }
+    int off;
+    if (b == 0 || en == s) off = 0;
+    else if (b == nb1 - 1) off = (int)(en - s);
+    else off = (int)(lower_bound_i32(b_col, s, en, b << kBlkShift) - s);
+    bp[i] = off;
   }
 }
 

@@ -1,8 +1,9 @@
 // Sorted-list (sparse) workspace for short rows: every intermediate product of a row is
-// appended to a small coordinate list in LDS (insert), the list is sorted by column with
-// a bitonic network (sort) and runs of equal columns are summed (merge).  This is the
-// expand / sort / reduce-by-key policy of the paper's table of library algorithms
-// (section 4.4) run at wavefront level, one row per GROUP lanes.
+// appended to a small coordinate list in LDS (insert), the list is put in column order (sort:
+// a bitonic network for columns alone, a count of the entries before each entry when values
+// travel along) and runs of equal columns are summed (merge).  This is the expand / sort /
+// reduce-by-key policy of the paper's table of library algorithms (section 4.4) run at
+// wavefront level, one row per GROUP lanes.
 #pragma once
 #include "common.hpp"
 

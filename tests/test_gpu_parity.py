@@ -83,6 +83,28 @@ def test_sorted_list_keys_too_wide_to_pack():
         run(A, B0, LIST, what="narrow sorted-list keys")
 
 
+def test_sorted_list_rows_with_many_a_entries():
+    # rows of up to 128 products made of many A entries with B rows of one or two entries: the one-wave class
+    # takes its A entries 64 at a time, and a batch of at most 16 entries deals products instead of entries
+    # to the lanes; 70 = a full batch and a short one, 16 / 17 = both sides of that limit
+    k = 300
+    degs = [70, 100, 17, 16, 15, 64, 65, 128, 1, 40] * 12
+    rowptr = np.zeros(len(degs) + 1, dtype=np.int64)
+    np.cumsum(degs, out=rowptr[1:])
+    nnz = int(rowptr[-1])
+    cols = np.concatenate([np.sort(W.rand_below(87, 1, np.arange(i * 1000, i * 1000 + 4 * d, dtype=np.uint64), k)[:d])
+                           for i, d in enumerate(degs)]).astype(np.int32)
+    A = W.CSR(len(degs), k, rowptr, cols, W.draw_values(nnz, -1.0, 1.0, np.float64, 87, 2))
+    lens = 1 + (np.arange(k) % 7 == 0)   # one entry per B row, two in every seventh
+    bp = np.zeros(k + 1, dtype=np.int64)
+    np.cumsum(lens, out=bp[1:])
+    bcol = W.rand_below(87, 3, np.arange(int(bp[-1]), dtype=np.uint64), 50).astype(np.int32)
+    B = W.CSR(k, 50, bp, bcol, W.draw_values(int(bp[-1]), -1.0, 1.0, np.float64, 87, 4))
+    for force in (AUTO, LIST):
+        st = run(A, B, force, what=f"many A entries, force={force}")
+    assert st["num_bin_rows"][1] >= 60
+
+
 def test_stencil_small_grid():
     a, b = W.config2(g=12)
     st = run(a, b, what="stencil 12^3")

@@ -46,7 +46,8 @@ constexpr int kCountMask = kSearchBit - 1;
 constexpr int kSearchCap = 11264;       // entries of a searched tile (column 4 B + sum 8 B each)
 constexpr int kSegCap = 1024;           // A entries described in LDS at a time (numeric)
 constexpr int kBlkWords = kBlkCols / 32;
-constexpr int kListStage = 320;          // entries that a wave gathers in LDS before writing them to the column list
+constexpr int kSymPieces = 1024;         // A entries that the symbolic kernel describes in LDS at a time
+constexpr int kListStage = kSymPieces * 5 / kDenseWaves;   // entries that a wave gathers in LDS (the piece walker's, free by then) before writing them to the column list
 constexpr int kListBatch = 4;           // column-list loads in flight per thread
 // every tile kind must fit the tile area of the numeric kernel
 static_assert((long long)kSearchCap * 12 <= kTileBudget, "searched tile: 4 B column + 8 B sum per entry");
@@ -84,13 +85,14 @@ struct RunRec { int row; unsigned first; int count, d; long long a0, list; };
 
 // Per-workgroup bookkeeping of the piece walker below.
 struct RowScratch {
-  long long start[kDenseThreads];   // first B entry of each A entry's piece
-  int plen[kDenseThreads];          // piece length
-  int cpre[kDenseThreads + 1];      // exclusive prefix of chunk counts (long pieces)
-  int spre[kDenseThreads + 1];      // exclusive prefix of lengths (short pieces)
+  long long start[kSymPieces];   // first B entry of each A entry's piece
+  int plen[kSymPieces];          // piece length
+  int cpre[kSymPieces + 1];      // exclusive prefix of chunk counts (long pieces)
+  int spre[kSymPieces + 1];      // exclusive prefix of lengths (short pieces)
   int red[2 * kDenseWaves];
   int s_row;
   int pad;
+  unsigned long long span_ip;       // products streamed since the owner last cleared it
   SPG_CLK(ClkLds clk;)
 };
 
@@ -115,7 +117,7 @@ __device__ __forceinline__ void block_excl_scan2(int a, int b, int& ea, int& eb,
 }
 
 // Walks every pair (A entry p of the row, B entry q of row a_col[p]) and calls
-// f(column).  range(k, s, en) may narrow the piece [s, en) of B row k first.  Up to 1024 A
+// f(column).  range(k, s, en) may narrow the piece [s, en) of B row k first.  Up to kSymPieces A
 // entries are described at once (one per thread); pieces of kShortLen or more are cut into
 // chunks of kChunk elements and the chunks are dealt to the 16 waves in contiguous shares,
 // each wave reading a chunk coalesced with kUnroll loads in flight per lane; the shorter
@@ -126,11 +128,12 @@ __device__ __forceinline__ void stream_columns(int64_t a0, int d, const int32_t*
                                                const int64_t* __restrict__ b_rp, const int32_t* __restrict__ b_col,
                                                RowScratch* rs, Range range, F f) {
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  for (int base = 0; base < d; base += kDenseThreads) {
+  static_assert(kSymPieces <= kDenseThreads, "a thread per described entry");
+  for (int base = 0; base < d; base += kSymPieces) {
     const int e = base + tid;
     int64_t s = 0;
     int len = 0;
-    if (e < d) {
+    if (e < d && tid < kSymPieces) {
       const int k = a_col[a0 + e];
       const Run<int64_t, 2> bounds = load_run<int64_t, 2>(b_rp + k);
       s = bounds.v[0];
@@ -140,13 +143,21 @@ __device__ __forceinline__ void stream_columns(int64_t a0, int d, const int32_t*
     }
     const int nch = len >= kShortLen ? (len + kChunk - 1) / kChunk : 0;
     const int sl = len < kShortLen ? len : 0;
+    if (Range::kNarrows) {   // (a narrowed walk covers a part of the row: its products are counted for the caller)
+      unsigned long long wl = (unsigned long long)len;
+#pragma unroll
+      for (int sh = 1; sh < kWave; sh <<= 1) wl += __shfl_xor(wl, sh, kWave);
+      if (lane == 0 && wl) atomicAdd(&rs->span_ip, wl);
+    }
     int ec, es, tc, ts;
     block_excl_scan2(nch, sl, ec, es, tc, ts, rs->red);
-    rs->start[tid] = s;
-    rs->plen[tid] = len;
-    rs->cpre[tid] = ec;
-    rs->spre[tid] = es;
-    if (tid == 0) { rs->cpre[kDenseThreads] = tc; rs->spre[kDenseThreads] = ts; }
+    if (tid < kSymPieces) {
+      rs->start[tid] = s;
+      rs->plen[tid] = len;
+      rs->cpre[tid] = ec;
+      rs->spre[tid] = es;
+    }
+    if (tid == 0) { rs->cpre[kSymPieces] = tc; rs->spre[kSymPieces] = ts; }
     __syncthreads();
     SPG_CLK(clk_mark(&rs->clk, 2); clk_add(&rs->clk, 18, 1); clk_add(&rs->clk, 19, (unsigned long long)tc);)
     if (tc > 0) {
@@ -154,7 +165,7 @@ __device__ __forceinline__ void stream_columns(int64_t a0, int d, const int32_t*
       int c = wave * per;
       const int cend = (c + per < tc) ? c + per : tc;
       if (c < cend) {
-        int lo = 0, hi = kDenseThreads;   // last entry whose first chunk is <= c
+        int lo = 0, hi = kSymPieces;   // last entry whose first chunk is <= c
         while (hi - lo > 1) {
           const int mid = (lo + hi) >> 1;
           if (rs->cpre[mid] <= c) lo = mid; else hi = mid;
@@ -184,7 +195,7 @@ __device__ __forceinline__ void stream_columns(int64_t a0, int d, const int32_t*
     }
     SPG_CLK(clk_mark(&rs->clk, 3);)
     for (int t = tid; t < ts; t += kDenseThreads) {
-      int lo = 0, hi = kDenseThreads;
+      int lo = 0, hi = kSymPieces;
       while (hi - lo > 1) {
         const int mid = (lo + hi) >> 1;
         if (rs->spre[mid] <= t) lo = mid; else hi = mid;
@@ -219,10 +230,22 @@ __global__ __launch_bounds__(256) void k_block_ptrs(int64_t rows, int nb1, const
 }
 
 struct NoRange {
+  static constexpr bool kNarrows = false;
   __device__ __forceinline__ void operator()(int, int64_t&, int64_t&) const {}
 };
 
+struct TableRange {   // ascending rows with the block-offset table: the entries in blocks [b0, b1)
+  static constexpr bool kNarrows = true;
+  const int* bp; int nb1; int b0, b1;
+  __device__ __forceinline__ void operator()(int k, int64_t& s, int64_t& en) const {
+    const int* row = bp + (int64_t)k * nb1;
+    en = s + row[b1];
+    s += row[b0];
+  }
+};
+
 struct SearchRange {   // binary search in an ascending row
+  static constexpr bool kNarrows = true;
   const int32_t* b_col; int lo; int64_t hi;
   __device__ __forceinline__ void operator()(int, int64_t& s, int64_t& en) const {
     if (en > s) {
@@ -278,18 +301,20 @@ __device__ __forceinline__ int prev_bit128(unsigned long long lo, unsigned long 
 // are grouped greedily into ranked tiles of at most kTileBudget bytes
 // (kRankBlkBytes per block + kRankEntryBytes per entry).  Records land in tp->rec, their number in tp->ntiles.
 // First part (wave 0): entry prefix over the blocks and the span's total.
+constexpr bool kSpanTwoHalves = kSpanBlocks > kWave;   // a lane plans one block, or two
+static_assert(kSpanBlocks == kWave || kSpanBlocks == 2 * kWave, "a span of 64 or 128 blocks");
 __device__ __forceinline__ void plan_head(TilePlan* tp, int nb, bool count_only) {
   const int l = lane_id();
   const int c0 = l < nb ? tp->blk_cnt[l] : 0;
-  const int c1 = l + 64 < nb ? tp->blk_cnt[l + 64] : 0;
+  const int c1 = (kSpanTwoHalves && l + 64 < nb) ? tp->blk_cnt[l + 64] : 0;
   const int i0 = wave_incl_scan(c0);
   const int t0 = __builtin_amdgcn_readlane(i0, 63);
-  const int i1 = wave_incl_scan(c1);
+  const int i1 = kSpanTwoHalves ? wave_incl_scan(c1) : 0;
   tp->cum[l] = i0 - c0;
-  tp->cum[l + 64] = t0 + i1 - c1;
+  if (kSpanTwoHalves) tp->cum[l + 64] = t0 + i1 - c1;
   if (l == 63) {
     const int total = t0 + i1;
-    tp->cum[128] = total;
+    tp->cum[kSpanBlocks] = total;
     tp->ntiles = 0;
     tp->ndirect = 0;
     if (count_only) tp->row_out += total;   // the row's numeric class needs no tiles
@@ -300,11 +325,11 @@ __device__ __forceinline__ void plan_head(TilePlan* tp, int nb, bool count_only)
 __device__ __forceinline__ void plan_tail(TilePlan* tp, int nb, int block0, int direct_min) {
   const int l = lane_id();
   const int c0 = l < nb ? tp->blk_cnt[l] : 0;
-  const int c1 = l + 64 < nb ? tp->blk_cnt[l + 64] : 0;
+  const int c1 = (kSpanTwoHalves && l + 64 < nb) ? tp->blk_cnt[l + 64] : 0;
   const unsigned long long dm0 = __ballot(c0 >= direct_min), dm1 = __ballot(c1 >= direct_min);
   const unsigned long long nm0 = __ballot(c0 > 0), nm1 = __ballot(c1 > 0);
 #pragma unroll
-  for (int half = 0; half < 2; ++half) {
+  for (int half = 0; half < (kSpanTwoHalves ? 2 : 1); ++half) {
     const int b = l + 64 * half;
     if (b < nb) {
       int lim = next_bit128(dm0, dm1, b);   // first direct block at or behind b
@@ -363,7 +388,7 @@ __global__ __launch_bounds__(kDenseThreads) void k_sym_dense(const int* __restri
                                                              int64_t n_cols, const int* __restrict__ ip, int* __restrict__ cnt,
                                                              TileRec* __restrict__ tiles, RunRec* __restrict__ runs,
                                                              int32_t* __restrict__ col_list, int direct_min, int no_tiles_ip,
-                                                             int search_ratio) {
+                                                             int search_ratio, const int* __restrict__ bp, int nb1) {
   extern __shared__ __align__(16) unsigned char smem[];
   unsigned* flags = reinterpret_cast<unsigned*>(smem);                               // kSymFlagWords
   RowScratch* rs = reinterpret_cast<RowScratch*>(smem + (size_t)kSymFlagWords * 4);
@@ -392,7 +417,7 @@ __global__ __launch_bounds__(kDenseThreads) void k_sym_dense(const int* __restri
         for (int w = tid; w < kSymFlagWords / 4; w += kDenseThreads) f4[w] = make_uint4(0, 0, 0, 0);
       }
       if (tid < kSpanBlocks) tp->blk_cnt[tid] = 0;
-      if (tid == 0) { tp->span_out0 = tp->row_out; tp->list_base = -1; }
+      if (tid == 0) { tp->span_out0 = tp->row_out; tp->list_base = -1; rs->span_ip = 0; }
       __syncthreads();
       SPG_CLK(clk_mark(&rs->clk, 1); clk_add(&rs->clk, 17, 1);)
       const int lo = (int)c0;
@@ -400,29 +425,35 @@ __global__ __launch_bounds__(kDenseThreads) void k_sym_dense(const int* __restri
       auto mark = [&](int c) {
         if (c >= lo && (int64_t)c < hi) atomicOr(&flags[(c - lo) >> 5], 1u << ((c - lo) & 31));
       };
-      if (n_cols > span && sorted)
+      if (n_cols > span && sorted && bp)
+        stream_columns(a0, d, a_col, b_rp, b_col, rs, TableRange{bp, nb1, (int)(c0 >> kBlkShift), (int)((c1 + kBlkCols - 1) >> kBlkShift)}, mark);
+      else if (n_cols > span && sorted)
         stream_columns(a0, d, a_col, b_rp, b_col, rs, SearchRange{b_col, lo, hi}, mark);
       else
         stream_columns(a0, d, a_col, b_rp, b_col, rs, NoRange{}, mark);
-      // entries per block: thread t owns flag words [32 t, 32 t + 32), 8 threads per block
+      // entries per block and per group: thread t owns kWordsPerThread consecutive flag words
       {
-        const uint4* f4 = reinterpret_cast<const uint4*>(flags) + tid * 8;
+        constexpr int kWordsPerThread = kSymFlagWords / kDenseThreads;
+        static_assert(kWordsPerThread % 4 == 0 && kGrpWords % kWordsPerThread == 0 && kBlkWords % kWordsPerThread == 0, "whole threads per group and block");
+        constexpr int kThreadsPerGroup = kGrpWords / kWordsPerThread, kThreadsPerBlock = kBlkWords / kWordsPerThread;
+        static_assert(kThreadsPerBlock <= kWave, "a block's threads sit in one wave");
+        const uint4* f4 = reinterpret_cast<const uint4*>(flags) + tid * (kWordsPerThread / 4);
         int local = 0;
 #pragma unroll
-        for (int q = 0; q < 8; ++q) {
+        for (int q = 0; q < kWordsPerThread / 4; ++q) {
           const uint4 v = f4[q];
           local += __popc(v.x) + __popc(v.y) + __popc(v.z) + __popc(v.w);
         }
-        local += __shfl_xor(local, 1, kWave);
-        if ((tid & 1) == 0) tp->grp[tid >> 1] = local;   // (32 words per thread: a pair of threads is a group)
-        local += __shfl_xor(local, 2, kWave);
-        local += __shfl_xor(local, 4, kWave);
-        if ((tid & 7) == 0) tp->blk_cnt[tid >> 3] = local;
+#pragma unroll
+        for (int sh = 1; sh < kThreadsPerGroup; sh <<= 1) local += __shfl_xor(local, sh, kWave);
+        if (tid % kThreadsPerGroup == 0) tp->grp[tid / kThreadsPerGroup] = local;
+#pragma unroll
+        for (int sh = kThreadsPerGroup; sh < kThreadsPerBlock; sh <<= 1) local += __shfl_xor(local, sh, kWave);
+        if (tid % kThreadsPerBlock == 0) tp->blk_cnt[tid / kThreadsPerBlock] = local;
       }
       __syncthreads();
       SPG_CLK(clk_mark(&rs->clk, 5);)
       const bool count_only = ip[row] <= no_tiles_ip;
-      const bool whole_row = n_cols <= span;
       const bool last_span = c1 >= n_cols;
       const int block0 = (int)(c0 >> kBlkShift);
       if (tid < kWave) {
@@ -434,17 +465,21 @@ __global__ __launch_bounds__(kDenseThreads) void k_sym_dense(const int* __restri
       if (tid == 0) {
         // Everything this span needs from the plan's shared lists, and the next row, in one round trip:
         // room for the entries in the column list (without it the numeric kernel rebuilds the flags
-        // itself), tile and run records.  A span that is the whole row, got room in the list and has at
+        // itself), tile and run records.  A span that got room in the list and has at
         // most kSearchCap entries and at most search_ratio products per entry becomes one searched tile
         // (the records planned above stay unused).
-        const int total = tp->cum[128];
+        const int total = tp->cum[kSpanBlocks];
         const int nt = tp->ntiles;
         const int nr = (nt + kRunTiles - 1) / kRunTiles;
         const bool want_list = !count_only && total > 0 && list_cap > 0;
         // a short row with little deduplication becomes one searched tile and needs its columns; every
         // other row keeps its flag words as they are (no decoding here, and far less memory for rows
         // with many entries) unless they would take much more room than the columns
-        const bool search_row = whole_row && total <= kSearchCap && nt > 1 && (long long)ip[row] <= (long long)search_ratio * total;
+        // (products of the span: counted by the walk when it covered a part of the row)
+        const long long span_products = (n_cols > span && sorted) ? (long long)rs->span_ip : (long long)ip[row];
+        // (a searched tile takes every product of its pieces: with unordered B rows the pieces are whole rows,
+        // so the tile must be the whole row)
+        const bool search_row = (sorted || n_cols <= span) && total <= kSearchCap && nt > 1 && span_products <= (long long)search_ratio * total;
         const int fwords = (words + 3) & ~3;
         const bool as_words = !search_row && (long long)fwords * kFlagWordsNum <= (long long)kFlagWordsDen * total;
         const unsigned long long need = as_words ? (unsigned long long)(span_rank_slots(words) + fwords)

@@ -356,7 +356,7 @@ int run_symbolic(spgemm_context* h, spgemm_plan_s* p, const spgemm_csr* A, const
       Timer t(h, SPGEMM_K_SYM_DENSE);
       hipLaunchKernelGGL(k_sym_dense, dim3(grid_for(rows_dense, 1, h->num_cus)), dim3(kDenseThreads), kSymDenseLds, s, p->perm_sym,
                          p->ctl, A->rowptr, A->colidx, B->rowptr, B->colidx, B->cols, p->ip, p->cnt, p->tiles, p->runs, p->col_list, h->direct_min,
-                         staged, h->search_ratio);
+                         staged, h->search_ratio, p->blk_ptr, p->blk_ptr_cols);
     }
     {
       Timer t(h, SPGEMM_K_BIN);

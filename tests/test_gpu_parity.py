@@ -185,11 +185,22 @@ def test_without_block_table_pieces_are_bisected(column_list):
 def test_wide_matrix_several_flag_list_spans_and_long_a_rows():
     # more than 2^20 columns (the symbolic flag list covers the row in several spans) and rows of A
     # with more entries than the numeric kernel keeps in registers
+    from paper_2404_04541_amd import binding as sg
     A = W.random_csr(24, 6000, 1500, 61)
     B = W.random_csr(6000, 2_500_000, 40, 62)
     for force in (AUTO, DENSE):
         st = run(A, B, force, what=f"wide force={force}")
         assert st["dense_tiles"] > 0
+    # shorter rows: every span of a row has few enough entries for one searched tile of its own
+    A2 = W.random_csr(40, 6000, 300, 63)
+    st = run(A2, B, DENSE, what="wide, searched tiles per span")
+    assert st["dense_search_tiles"] > 40, "more searched tiles than rows: they are per span"
+    # the same without the block-offset table (piece bounds by bisection) and with unordered B rows (whole
+    # rows are walked for every span; no searched tiles then, a tile would see products of other spans)
+    run(A2, B, DENSE, what="wide, no block table", options={sg.OPT_BLOCK_TABLE: 0})
+    Bu = W.random_csr(6000, 2_500_000, 40, 62, sort_rows=False)
+    st = run(A2, Bu, DENSE, what="wide, unordered B")
+    assert st["dense_search_tiles"] == 0
 
 
 @pytest.mark.parametrize("direct_min", [256, 1 << 20])

@@ -159,7 +159,10 @@ __global__ __launch_bounds__(256) void k_esc(const int* __restrict__ perm, const
     if constexpr (!NUMERIC) {
       // symbolic: the columns alone go through the bitonic network (4 bytes per entry and stage); a
       // position is a head when its column differs from its left neighbour
-      bitonic_sort_lds<GROUP, CAP, double>(keys, static_cast<double*>(nullptr), CAP, gl);
+      // (half the network when no row of the wave reaches into its second half; both sizes are compile-time
+      // constants so that the stages unroll)
+      if (two) bitonic_sort_lds<GROUP, CAP, double>(keys, static_cast<double*>(nullptr), CAP, gl);
+      else bitonic_sort_lds<GROUP, CAP, double>(keys, static_cast<double*>(nullptr), GROUP, gl);
       const int i0 = 2 * gl, i1 = 2 * gl + 1;
       const int k0 = keys[i0], k1 = keys[i1];
       const int kprev = i0 > 0 ? keys[i0 - 1] : -1;

@@ -188,8 +188,16 @@ __global__ __launch_bounds__(256) void k_hash(const int* __restrict__ perm, cons
       while (nsort < filled) nsort <<= 1;
       for (int t = filled + gl; t < nsort; t += GROUP) keys[t] = kPadKey;
       group_sync<GROUP>();
-      if (packable) bitonic_sort_lds<GROUP, H, double>(keys, nullptr, nsort, gl);
-      else bitonic_sort_lds<GROUP, H, double>(keys, vals, nsort, gl);
+      // (the usual sizes as compile-time constants, so that the network's stages unroll)
+      if (packable) {
+        if (nsort == H) bitonic_sort_lds<GROUP, H, double>(keys, nullptr, H, gl);
+        else if (nsort == H / 2) bitonic_sort_lds<GROUP, H, double>(keys, nullptr, H / 2, gl);
+        else if (nsort == H / 4) bitonic_sort_lds<GROUP, H, double>(keys, nullptr, H / 4, gl);
+        else if (nsort == H / 8) bitonic_sort_lds<GROUP, H, double>(keys, nullptr, H / 8, gl);
+        else bitonic_sort_lds<GROUP, H, double>(keys, nullptr, nsort, gl);
+      } else {
+        bitonic_sort_lds<GROUP, H, double>(keys, vals, nsort, gl);
+      }
       if (live) {
         const int64_t out = c_rp[row];
         const int n = (int)(c_rp[row + 1] - out);

@@ -125,6 +125,8 @@ __global__ __launch_bounds__(256) void k_hash(const int* __restrict__ perm, cons
         if (NUMERIC) pav[gl] = av;
         if (gl == 0) pre[GROUP] = total;
         group_sync<GROUP>();
+        const int nent = d - base < GROUP ? d - base : GROUP;
+        const float per_product = total > 0 ? (float)nent / (float)total : 0.0f;   // entries per product
         for (int f0 = gl; f0 < total; f0 += GROUP * kHashUnroll) {
           int col[kHashUnroll];
           double prod[kHashUnroll];
@@ -134,12 +136,23 @@ __global__ __launch_bounds__(256) void k_hash(const int* __restrict__ perm, cons
             col[u] = -1;
             prod[u] = 0.0;
             if (f < total) {
-              int lo = 0, hi = GROUP;   // last entry whose first product is <= f
-              while (hi - lo > 1) {
-                const int mid = (lo + hi) >> 1;
-                if (pre[mid] <= f) lo = mid; else hi = mid;
+              // entry of product f: the last one whose first product is <= f.  With B rows of similar length it
+              // sits where the product's share of the total points, or next to it; otherwise it is bisected
+              int lo = (int)((float)f * per_product);
+              lo = lo < GROUP - 1 ? lo : GROUP - 1;
+              int first = pre[lo], next = pre[lo + 1];
+              if (first > f) { --lo; next = first; first = pre[lo]; }
+              else if (next <= f) { ++lo; first = next; next = pre[lo + 1]; }
+              if (first > f || next <= f) {
+                int hi = GROUP;
+                lo = 0;
+                while (hi - lo > 1) {
+                  const int mid = (lo + hi) >> 1;
+                  if (pre[mid] <= f) lo = mid; else hi = mid;
+                }
+                first = pre[lo];
               }
-              const int64_t q = pbs[lo] + (f - pre[lo]);
+              const int64_t q = pbs[lo] + (f - first);
               col[u] = b_col[q];
               if (NUMERIC) prod[u] = pav[lo] * (double)b_val[q];
             }

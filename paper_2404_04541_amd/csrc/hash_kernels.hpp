@@ -26,6 +26,10 @@ __device__ __forceinline__ int hash_find_or_insert(int* keys, int key, int& is_n
 
 constexpr int kHashUnroll = 4;
 
+// An A entry of the row being inserted: its products are [first, next) of the row's product index space,
+// its B row starts at bs.
+struct __align__(16) HashEntry { int first, next; int64_t bs; };
+
 // Exclusive scan over a group of GROUP threads (a wave, or the workgroup of 256), with the total.
 // part: GROUP / 64 + 1 ints of LDS of the group.  Contains the group's synchronisation when GROUP > 64.
 template <int GROUP>
@@ -68,10 +72,10 @@ __global__ __launch_bounds__(256) void k_hash(const int* __restrict__ perm, cons
   // per group: the entries being inserted (length prefix, B row start, a_ik) and scan partials
   unsigned char* extra = reinterpret_cast<unsigned char*>(counters + kGroups);
   extra += (8 - (reinterpret_cast<size_t>(extra) & 7)) & 7;
-  int64_t* all_pbs = reinterpret_cast<int64_t*>(extra);
-  double* all_pav = reinterpret_cast<double*>(all_pbs + kGroups * GROUP);
-  int* all_pre = reinterpret_cast<int*>(all_pav + kGroups * GROUP);
-  int* part = all_pre + kGroups * (GROUP + 1);
+  extra += (16 - (reinterpret_cast<size_t>(extra) & 15)) & 15;
+  HashEntry* all_ent = reinterpret_cast<HashEntry*>(extra);
+  double* all_pav = reinterpret_cast<double*>(all_ent + kGroups * GROUP);
+  int* part = reinterpret_cast<int*>(all_pav + kGroups * GROUP);
   if (ctl->error) return;
   const unsigned first = ctl->offset[phase][bin];
   const unsigned nrows = ctl->offset[phase][bin + 1] - first;
@@ -79,9 +83,8 @@ __global__ __launch_bounds__(256) void k_hash(const int* __restrict__ perm, cons
   const int gl = threadIdx.x % GROUP;
   int* keys = all_keys + g * H;
   double* vals = NUMERIC ? all_vals + g * H : nullptr;
-  int64_t* pbs = all_pbs + g * GROUP;
+  HashEntry* ent = all_ent + g * GROUP;
   double* pav = all_pav + g * GROUP;
-  int* pre = all_pre + g * (GROUP + 1);
   const unsigned ngroups = gridDim.x * kGroups;
   const unsigned rounds = (nrows + ngroups - 1) / ngroups;
   for (unsigned r = 0; r < rounds; ++r) {
@@ -120,10 +123,8 @@ __global__ __launch_bounds__(256) void k_hash(const int* __restrict__ perm, cons
         }
         int total;
         const int excl = group_excl_scan<GROUP>(len, total, part + g * (GROUP / kWave + 1));
-        pre[gl] = excl;
-        pbs[gl] = bs;
+        ent[gl] = HashEntry{excl, excl + len, bs};
         if (NUMERIC) pav[gl] = av;
-        if (gl == 0) pre[GROUP] = total;
         group_sync<GROUP>();
         const int nent = d - base < GROUP ? d - base : GROUP;
         const float per_product = total > 0 ? (float)nent / (float)total : 0.0f;   // entries per product
@@ -140,19 +141,19 @@ __global__ __launch_bounds__(256) void k_hash(const int* __restrict__ perm, cons
               // sits where the product's share of the total points, or next to it; otherwise it is bisected
               int lo = (int)((float)f * per_product);
               lo = lo < GROUP - 1 ? lo : GROUP - 1;
-              int first = pre[lo], next = pre[lo + 1];
-              if (first > f) { --lo; next = first; first = pre[lo]; }
-              else if (next <= f) { ++lo; first = next; next = pre[lo + 1]; }
-              if (first > f || next <= f) {
+              HashEntry en = ent[lo];   // (one 16-byte read: first product, end, start in B)
+              if (en.first > f) en = ent[--lo];
+              else if (en.next <= f) en = ent[++lo];   // (f < total: an entry with products follows)
+              if (en.first > f || en.next <= f) {
                 int hi = GROUP;
                 lo = 0;
                 while (hi - lo > 1) {
                   const int mid = (lo + hi) >> 1;
-                  if (pre[mid] <= f) lo = mid; else hi = mid;
+                  if (ent[mid].first <= f) lo = mid; else hi = mid;
                 }
-                first = pre[lo];
+                en = ent[lo];
               }
-              const int64_t q = pbs[lo] + (f - first);
+              const int64_t q = en.bs + (f - en.first);
               col[u] = b_col[q];
               if (NUMERIC) prod[u] = pav[lo] * (double)b_val[q];
             }
@@ -228,7 +229,7 @@ __global__ __launch_bounds__(256) void k_hash(const int* __restrict__ perm, cons
 template <int GROUP, int LOGH, bool NUMERIC>
 constexpr size_t hash_lds_bytes() {
   return (size_t)(256 / GROUP) * (1u << LOGH) * (sizeof(int) + (NUMERIC ? sizeof(double) : 0)) + (256 / GROUP) * sizeof(int) + 8 +
-         (size_t)256 * (8 + 8 + 4) + (256 / GROUP) * 4 + (size_t)(256 / GROUP) * (GROUP / kWave + 1) * 4;
+         16 + (size_t)256 * (sizeof(HashEntry) + 8) + (size_t)(256 / GROUP) * (GROUP / kWave + 1) * 4;
 }
 
 }  // namespace spg

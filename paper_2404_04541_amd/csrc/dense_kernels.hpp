@@ -116,18 +116,135 @@ __device__ __forceinline__ void block_excl_scan2(int a, int b, int& ea, int& eb,
   eb = pb + ib - b;
 }
 
+constexpr int kChunkUnroll = 8;
+
+// The non-empty pieces that a pass walks, in LDS: first B entry, exclusive prefix of the chunk counts (np + 1
+// values), length and (numeric) a_ik of every piece.
+template <typename T>
+struct PieceList {
+  const long long* s;
+  const int* cpre;
+  const int* len;
+  const T* av;
+};
+
+__device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ long long uni64(long long v) {
+  const unsigned lo = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(unsigned long long)v);
+  const unsigned hi = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)((unsigned long long)v >> 32));
+  return (long long)(((unsigned long long)hi << 32) | lo);
+}
+
+__device__ __forceinline__ int lane_get(int v, int lane) { return __builtin_amdgcn_readlane(v, lane); }
+__device__ __forceinline__ long long lane_get(long long v, int lane) {
+  const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(unsigned long long)v, lane);
+  const unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)((unsigned long long)v >> 32), lane);
+  return (long long)(((unsigned long long)hi << 32) | lo);
+}
+__device__ __forceinline__ float lane_get(float v, int lane) { return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane)); }
+__device__ __forceinline__ double lane_get(double v, int lane) { return __longlong_as_double(lane_get(__double_as_longlong(v), lane)); }
+
+// Visits every element of the pieces once.  A piece is cut into chunks of 64 elements; the
+// chunks of all pieces are dealt to the waves in contiguous shares; a wave reads a chunk
+// coalesced (one element per lane) with kChunkUnroll chunks in flight.  Everything that
+// describes a chunk is wave-uniform: the descriptors of the pieces that a batch of chunks can
+// touch are fetched from LDS by one lane each and handed out with readlane, so a batch costs
+// one LDS round trip before its loads are issued.  f(column, a, b) is called per element
+// (a, b only meaningful when WITH_VALUES); g(columns, a's, b's) gets a whole batch of
+// kChunkUnroll elements per lane (column -1: no element).
+template <bool WITH_VALUES, typename T, class G>
+__device__ __forceinline__ void chunk_pass_batches(int np, int nchunks, const PieceList<T> pl, const int32_t* __restrict__ b_col,
+                                                   const T* __restrict__ b_val, G g) {
+  const int wave = uni(threadIdx.x >> 6), lane = threadIdx.x & 63;
+  np = uni(np);
+  nchunks = uni(nchunks);
+  const int per = (nchunks + kDenseWaves - 1) / kDenseWaves;
+  int c = wave * per;
+  const int cend = c + per < nchunks ? c + per : nchunks;
+  if (c >= cend) return;
+  int p;
+  {
+    int lo = 0, hi = np;   // last piece whose first chunk is <= c
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (uni(pl.cpre[mid]) <= c) lo = mid; else hi = mid;
+    }
+    p = lo;
+  }
+  for (; c < cend; c += kChunkUnroll) {
+    // lane i describes piece p + i (a batch of kChunkUnroll chunks touches at most that many pieces)
+    const int pi = p + lane < np ? p + lane : np;
+    const int pj = p + lane < np ? p + lane : np - 1;
+    const int d_first = pl.cpre[pi];
+    const int d_len = pl.len[pj];
+    const long long d_s = pl.s[pj];
+    const T d_av = WITH_VALUES ? pl.av[pj] : T(0);
+    int q = 0;
+    // the piece in hand (wave-uniform; re-read from the lanes only when the piece changes)
+    int q_first = lane_get(d_first, 0), q_next = lane_get(d_first, 1), q_len = lane_get(d_len, 0);
+    const int32_t* pc = b_col + lane_get(d_s, 0);
+    const T* pv = b_val + lane_get(d_s, 0);
+    T q_av = WITH_VALUES ? lane_get(d_av, 0) : T(0);
+    int col[kChunkUnroll];
+    T bv[kChunkUnroll], au[kChunkUnroll];
+#pragma unroll
+    for (int u = 0; u < kChunkUnroll; ++u) {
+      const int cu = c + u;
+      col[u] = -1;
+      bv[u] = T(0);
+      au[u] = T(0);
+      if (cu < cend) {
+        if (cu >= q_next) {   // every piece has at least one chunk: one step suffices
+          ++q;
+          q_first = q_next;
+          q_next = lane_get(d_first, q + 1);
+          q_len = lane_get(d_len, q);
+          pc = b_col + lane_get(d_s, q);
+          pv = b_val + lane_get(d_s, q);
+          if (WITH_VALUES) q_av = lane_get(d_av, q);
+        }
+        const int off = (cu - q_first) * kWave + lane;
+        // (wave-uniform piece start + 32-bit lane offset: scalar base, one vector offset)
+        if (off < q_len) {
+          // (a piece is far shorter than 2^30 elements: the byte offset fits 32 bits, which lets the
+          // load take the scalar base plus one vector offset)
+          const unsigned byte_off = (unsigned)off * (unsigned)sizeof(int32_t);
+          col[u] = *reinterpret_cast<const int32_t*>(reinterpret_cast<const char*>(pc) + byte_off);
+          if (WITH_VALUES) bv[u] = *reinterpret_cast<const T*>(reinterpret_cast<const char*>(pv) + (unsigned)off * (unsigned)sizeof(T));
+        }
+        au[u] = q_av;
+      }
+    }
+    p += q;
+    g(col, au, bv);
+  }
+}
+
+// chunk_pass with a functor f(column, a, b) per element.
+template <bool WITH_VALUES, typename T, class F>
+__device__ __forceinline__ void chunk_pass(int np, int nchunks, const PieceList<T> pl, const int32_t* __restrict__ b_col,
+                                           const T* __restrict__ b_val, F f) {
+  chunk_pass_batches<WITH_VALUES, T>(np, nchunks, pl, b_col, b_val,
+                                     [&](const int (&col)[kChunkUnroll], const T (&au)[kChunkUnroll], const T (&bv)[kChunkUnroll]) {
+#pragma unroll
+                                       for (int u = 0; u < kChunkUnroll; ++u)
+                                         if (col[u] >= 0) f(col[u], au[u], bv[u]);
+                                     });
+}
+
 // Walks every pair (A entry p of the row, B entry q of row a_col[p]) and calls
 // f(column).  range(k, s, en) may narrow the piece [s, en) of B row k first.  Up to kSymPieces A
-// entries are described at once (one per thread); pieces of kShortLen or more are cut into
-// chunks of kChunk elements and the chunks are dealt to the 16 waves in contiguous shares,
-// each wave reading a chunk coalesced with kUnroll loads in flight per lane; the shorter
-// pieces are concatenated and walked by all threads, a thread finding its piece by a search
-// over the prefix of lengths.  Contains barriers: every thread of the workgroup must call it.
-template <class Range, class F>
+// entries are described at once (one per thread).  Pieces of kShortLen or more are compacted to the
+// front of the scratch arrays and walked like the numeric kernel's pieces: in chunks of 64 elements,
+// dealt to the 16 waves in contiguous shares, kChunkUnroll chunks of whatever pieces in flight per
+// wave.  The shorter pieces are compacted to the back and walked by all threads as one index space,
+// a thread finding its piece by a search over the prefix of their lengths.
+// Contains barriers: every thread of the workgroup must call it.
+template <class Range, class F, class FB>
 __device__ __forceinline__ void stream_columns(int64_t a0, int d, const int32_t* __restrict__ a_col,
                                                const int64_t* __restrict__ b_rp, const int32_t* __restrict__ b_col,
-                                               RowScratch* rs, Range range, F f) {
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+                                               RowScratch* rs, Range range, F f, FB fb) {
+  const int tid = threadIdx.x, lane = tid & 63;
   static_assert(kSymPieces <= kDenseThreads, "a thread per described entry");
   for (int base = 0; base < d; base += kSymPieces) {
     const int e = base + tid;
@@ -141,66 +258,40 @@ __device__ __forceinline__ void stream_columns(int64_t a0, int d, const int32_t*
       range(k, s, en);
       len = (int)(en - s);
     }
-    const int nch = len >= kShortLen ? (len + kChunk - 1) / kChunk : 0;
-    const int sl = len < kShortLen ? len : 0;
+    const bool is_long = len >= kShortLen;
+    const int nch = is_long ? (len + kWave - 1) >> 6 : 0;
+    const int sl = is_long ? 0 : len;
     if (Range::kNarrows) {   // (a narrowed walk covers a part of the row: its products are counted for the caller)
       unsigned long long wl = (unsigned long long)len;
 #pragma unroll
       for (int sh = 1; sh < kWave; sh <<= 1) wl += __shfl_xor(wl, sh, kWave);
       if (lane == 0 && wl) atomicAdd(&rs->span_ip, wl);
     }
-    int ec, es, tc, ts;
-    block_excl_scan2(nch, sl, ec, es, tc, ts, rs->red);
-    if (tid < kSymPieces) {
-      rs->start[tid] = s;
-      rs->plen[tid] = len;
-      rs->cpre[tid] = ec;
-      rs->spre[tid] = es;
+    int li, ec, nl, tc, sj, es, nshort, ts;
+    block_excl_scan2(is_long ? 1 : 0, nch, li, ec, nl, tc, rs->red);
+    block_excl_scan2(sl > 0 ? 1 : 0, sl, sj, es, nshort, ts, rs->red);
+    if (is_long) {
+      rs->start[li] = s;
+      rs->plen[li] = len;
+      rs->cpre[li] = ec;
+    } else if (sl > 0) {   // (long pieces fill the start array from the front, short ones from the back)
+      rs->start[kSymPieces - 1 - sj] = s;
+      rs->spre[sj] = es;
     }
-    if (tid == 0) { rs->cpre[kSymPieces] = tc; rs->spre[kSymPieces] = ts; }
+    if (tid == 0) { rs->cpre[nl] = tc; rs->spre[nshort] = ts; }
     __syncthreads();
     SPG_CLK(clk_mark(&rs->clk, 2); clk_add(&rs->clk, 18, 1); clk_add(&rs->clk, 19, (unsigned long long)tc);)
-    if (tc > 0) {
-      const int per = (tc + kDenseWaves - 1) / kDenseWaves;
-      int c = wave * per;
-      const int cend = (c + per < tc) ? c + per : tc;
-      if (c < cend) {
-        int lo = 0, hi = kSymPieces;   // last entry whose first chunk is <= c
-        while (hi - lo > 1) {
-          const int mid = (lo + hi) >> 1;
-          if (rs->cpre[mid] <= c) lo = mid; else hi = mid;
-        }
-        int ent = lo;
-        while (c < cend) {
-          const int cnext = rs->cpre[ent + 1];
-          if (c >= cnext) { ++ent; continue; }
-          const int64_t s_e = rs->start[ent];
-          const int len_e = rs->plen[ent];
-          const int cfirst = rs->cpre[ent];
-          const int cstop = cnext < cend ? cnext : cend;
-          for (; c < cstop; ++c) {
-            const int off = (c - cfirst) * kChunk + lane;
-            int col[kUnroll];
-#pragma unroll
-            for (int u = 0; u < kUnroll; ++u) {
-              const int idx = off + u * kWave;
-              col[u] = idx < len_e ? b_col[s_e + idx] : -1;
-            }
-#pragma unroll
-            for (int u = 0; u < kUnroll; ++u)
-              if (col[u] >= 0) f(col[u]);
-          }
-        }
-      }
-    }
+    if (tc > 0)
+      chunk_pass_batches<false, int>(nl, tc, PieceList<int>{rs->start, rs->cpre, rs->plen, nullptr}, b_col, static_cast<const int*>(nullptr),
+                                     [&](const int (&c)[kChunkUnroll], const int (&)[kChunkUnroll], const int (&)[kChunkUnroll]) { fb(c); });
     SPG_CLK(clk_mark(&rs->clk, 3);)
     for (int t = tid; t < ts; t += kDenseThreads) {
-      int lo = 0, hi = kSymPieces;
+      int lo = 0, hi = nshort;   // last short piece whose first element is <= t
       while (hi - lo > 1) {
         const int mid = (lo + hi) >> 1;
         if (rs->spre[mid] <= t) lo = mid; else hi = mid;
       }
-      f(b_col[rs->start[lo] + (t - rs->spre[lo])]);
+      f(b_col[rs->start[kSymPieces - 1 - lo] + (t - rs->spre[lo])]);
     }
     __syncthreads();
     SPG_CLK(clk_mark(&rs->clk, 4);)
@@ -425,12 +516,28 @@ __global__ __launch_bounds__(kDenseThreads) void k_sym_dense(const int* __restri
       auto mark = [&](int c) {
         if (c >= lo && (int64_t)c < hi) atomicOr(&flags[(c - lo) >> 5], 1u << ((c - lo) & 31));
       };
+      // a batch of columns: the flag words are read first (reads of one address are broadcast), and only bits
+      // that are not set yet go through the atomic (hub columns are set early and hit by most pieces)
+      auto mark_batch = [&](const int (&c)[kChunkUnroll]) {
+        unsigned w[kChunkUnroll];
+#pragma unroll
+        for (int u = 0; u < kChunkUnroll; ++u) {
+          const bool ok = c[u] >= lo && (int64_t)c[u] < hi;
+          w[u] = flags[ok ? (c[u] - lo) >> 5 : 0];
+        }
+#pragma unroll
+        for (int u = 0; u < kChunkUnroll; ++u) {
+          const bool ok = c[u] >= lo && (int64_t)c[u] < hi;
+          const unsigned bit = 1u << ((c[u] - lo) & 31);
+          if (ok && !(w[u] & bit)) atomicOr(&flags[(c[u] - lo) >> 5], bit);
+        }
+      };
       if (n_cols > span && sorted && bp)
-        stream_columns(a0, d, a_col, b_rp, b_col, rs, TableRange{bp, nb1, (int)(c0 >> kBlkShift), (int)((c1 + kBlkCols - 1) >> kBlkShift)}, mark);
+        stream_columns(a0, d, a_col, b_rp, b_col, rs, TableRange{bp, nb1, (int)(c0 >> kBlkShift), (int)((c1 + kBlkCols - 1) >> kBlkShift)}, mark, mark_batch);
       else if (n_cols > span && sorted)
-        stream_columns(a0, d, a_col, b_rp, b_col, rs, SearchRange{b_col, lo, hi}, mark);
+        stream_columns(a0, d, a_col, b_rp, b_col, rs, SearchRange{b_col, lo, hi}, mark, mark_batch);
       else
-        stream_columns(a0, d, a_col, b_rp, b_col, rs, NoRange{}, mark);
+        stream_columns(a0, d, a_col, b_rp, b_col, rs, NoRange{}, mark, mark_batch);
       // entries per block and per group: thread t owns kWordsPerThread consecutive flag words
       {
         constexpr int kWordsPerThread = kSymFlagWords / kDenseThreads;
@@ -645,112 +752,6 @@ struct NumScratch {
   SPG_CLK(ClkLds clk;)
 };
 
-constexpr int kChunkUnroll = 8;
-
-__device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
-__device__ __forceinline__ long long uni64(long long v) {
-  const unsigned lo = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(unsigned long long)v);
-  const unsigned hi = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)((unsigned long long)v >> 32));
-  return (long long)(((unsigned long long)hi << 32) | lo);
-}
-
-__device__ __forceinline__ int lane_get(int v, int lane) { return __builtin_amdgcn_readlane(v, lane); }
-__device__ __forceinline__ long long lane_get(long long v, int lane) {
-  const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(unsigned long long)v, lane);
-  const unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)((unsigned long long)v >> 32), lane);
-  return (long long)(((unsigned long long)hi << 32) | lo);
-}
-__device__ __forceinline__ float lane_get(float v, int lane) { return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane)); }
-__device__ __forceinline__ double lane_get(double v, int lane) { return __longlong_as_double(lane_get(__double_as_longlong(v), lane)); }
-
-// Visits every element of the pieces once.  A piece is cut into chunks of 64 elements; the
-// chunks of all pieces are dealt to the waves in contiguous shares; a wave reads a chunk
-// coalesced (one element per lane) with kChunkUnroll chunks in flight.  Everything that
-// describes a chunk is wave-uniform: the descriptors of the pieces that a batch of chunks can
-// touch are fetched from LDS by one lane each and handed out with readlane, so a batch costs
-// one LDS round trip before its loads are issued.  f(column, a, b) is called per element
-// (a, b only meaningful when WITH_VALUES); g(columns, a's, b's) gets a whole batch of
-// kChunkUnroll elements per lane (column -1: no element).
-template <bool WITH_VALUES, typename T, class G>
-__device__ __forceinline__ void chunk_pass_batches(int np, int nchunks, const NumScratch<T>* ns, const int32_t* __restrict__ b_col,
-                                                   const T* __restrict__ b_val, G g) {
-  const int wave = uni(threadIdx.x >> 6), lane = threadIdx.x & 63;
-  np = uni(np);
-  nchunks = uni(nchunks);
-  const int per = (nchunks + kDenseWaves - 1) / kDenseWaves;
-  int c = wave * per;
-  const int cend = c + per < nchunks ? c + per : nchunks;
-  if (c >= cend) return;
-  int p;
-  {
-    int lo = 0, hi = np;   // last piece whose first chunk is <= c
-    while (hi - lo > 1) {
-      const int mid = (lo + hi) >> 1;
-      if (uni(ns->c_cpre[mid]) <= c) lo = mid; else hi = mid;
-    }
-    p = lo;
-  }
-  for (; c < cend; c += kChunkUnroll) {
-    // lane i describes piece p + i (a batch of kChunkUnroll chunks touches at most that many pieces)
-    const int pi = p + lane < np ? p + lane : np;
-    const int pj = p + lane < np ? p + lane : np - 1;
-    const int d_first = ns->c_cpre[pi];
-    const int d_len = ns->c_len[pj];
-    const long long d_s = ns->c_s[pj];
-    const T d_av = WITH_VALUES ? ns->c_av[pj] : T(0);
-    int q = 0;
-    // the piece in hand (wave-uniform; re-read from the lanes only when the piece changes)
-    int q_first = lane_get(d_first, 0), q_next = lane_get(d_first, 1), q_len = lane_get(d_len, 0);
-    const int32_t* pc = b_col + lane_get(d_s, 0);
-    const T* pv = b_val + lane_get(d_s, 0);
-    T q_av = WITH_VALUES ? lane_get(d_av, 0) : T(0);
-    int col[kChunkUnroll];
-    T bv[kChunkUnroll], au[kChunkUnroll];
-#pragma unroll
-    for (int u = 0; u < kChunkUnroll; ++u) {
-      const int cu = c + u;
-      col[u] = -1;
-      bv[u] = T(0);
-      au[u] = T(0);
-      if (cu < cend) {
-        if (cu >= q_next) {   // every piece has at least one chunk: one step suffices
-          ++q;
-          q_first = q_next;
-          q_next = lane_get(d_first, q + 1);
-          q_len = lane_get(d_len, q);
-          pc = b_col + lane_get(d_s, q);
-          pv = b_val + lane_get(d_s, q);
-          if (WITH_VALUES) q_av = lane_get(d_av, q);
-        }
-        const int off = (cu - q_first) * kWave + lane;
-        // (wave-uniform piece start + 32-bit lane offset: scalar base, one vector offset)
-        if (off < q_len) {
-          // (a piece is far shorter than 2^30 elements: the byte offset fits 32 bits, which lets the
-          // load take the scalar base plus one vector offset)
-          const unsigned byte_off = (unsigned)off * (unsigned)sizeof(int32_t);
-          col[u] = *reinterpret_cast<const int32_t*>(reinterpret_cast<const char*>(pc) + byte_off);
-          if (WITH_VALUES) bv[u] = *reinterpret_cast<const T*>(reinterpret_cast<const char*>(pv) + (unsigned)off * (unsigned)sizeof(T));
-        }
-        au[u] = q_av;
-      }
-    }
-    p += q;
-    g(col, au, bv);
-  }
-}
-
-// chunk_pass with a functor f(column, a, b) per element.
-template <bool WITH_VALUES, typename T, class F>
-__device__ __forceinline__ void chunk_pass(int np, int nchunks, const NumScratch<T>* ns, const int32_t* __restrict__ b_col,
-                                           const T* __restrict__ b_val, F f) {
-  chunk_pass_batches<WITH_VALUES, T>(np, nchunks, ns, b_col, b_val,
-                                     [&](const int (&col)[kChunkUnroll], const T (&au)[kChunkUnroll], const T (&bv)[kChunkUnroll]) {
-#pragma unroll
-                                       for (int u = 0; u < kChunkUnroll; ++u)
-                                         if (col[u] >= 0) f(col[u], au[u], bv[u]);
-                                     });
-}
-
 // The piece [s, s + len) of B row k that falls into the tile (blocks [b0, b1), columns [t_lo, t_hi)).
 __device__ __forceinline__ void piece_range(int k, long long rs, long long re, int b0, int b1, int t_lo, int64_t t_hi, bool sorted,
                                             const int* __restrict__ bp, int nb1, const int32_t* __restrict__ b_col,
@@ -919,7 +920,7 @@ __device__ __forceinline__ void num_dense_run(const RunRec rr, NumScratch<T>* ns
         if (nseg > 1) seg_piece(sg, s, len, av);
         int np, nchunks;
         tile_pieces(ns, s, len, av, np, nchunks);   // (its barriers also publish cols and the cleared sums)
-        chunk_pass_batches<true, T>(np, nchunks, ns, b_col, b_val,
+        chunk_pass_batches<true, T>(np, nchunks, PieceList<T>{ns->c_s, ns->c_cpre, ns->c_len, ns->c_av}, b_col, b_val,
                                     [&](const int (&c)[kChunkUnroll], const T (&a)[kChunkUnroll], const T (&b)[kChunkUnroll]) {
           // last position whose column is <= c (the column is in the list); four bisections
           // advance in lockstep so that their LDS reads overlap
@@ -964,7 +965,7 @@ __device__ __forceinline__ void num_dense_run(const RunRec rr, NumScratch<T>* ns
         int np, nchunks;
         tile_pieces(ns, s, len, av, np, nchunks);
         SPG_CLK(clk_mark(&ns->clk, 7);)
-        chunk_pass<true, T>(np, nchunks, ns, b_col, b_val, [&](int c, T a, T b) {
+        chunk_pass<true, T>(np, nchunks, PieceList<T>{ns->c_s, ns->c_cpre, ns->c_len, ns->c_av}, b_col, b_val, [&](int c, T a, T b) {
           if (!CHECK || (c >= t_lo && (int64_t)c < t_hi)) {
             const int rel = c - t_lo;
             if (!have_list && !have_words) atomicOr(&flags[rel >> 5], 1u << (rel & 31));
@@ -1101,7 +1102,7 @@ __device__ __forceinline__ void num_dense_run(const RunRec rr, NumScratch<T>* ns
         T av = my_av;
         if (nseg > 1) seg_piece(sg, s, len, av);
         tile_pieces(ns, s, len, av, np, nchunks);
-        chunk_pass<false, T>(np, nchunks, ns, b_col, b_val, [&](int c, T, T) {
+        chunk_pass<false, T>(np, nchunks, PieceList<T>{ns->c_s, ns->c_cpre, ns->c_len, ns->c_av}, b_col, b_val, [&](int c, T, T) {
           if (!CHECK || (c >= t_lo && (int64_t)c < t_hi)) {
             const int rel = c - t_lo;
             atomicOr(&fc[rel >> 5].x, 1u << (rel & 31));
@@ -1165,7 +1166,7 @@ __device__ __forceinline__ void num_dense_run(const RunRec rr, NumScratch<T>* ns
             __hip_atomic_fetch_add(&acc[rank], (double)a * (double)b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
           }
         };
-        chunk_pass<true, T>(np, nchunks, ns, b_col, b_val, add);
+        chunk_pass<true, T>(np, nchunks, PieceList<T>{ns->c_s, ns->c_cpre, ns->c_len, ns->c_av}, b_col, b_val, add);
         if (nseg > 1) __syncthreads();
       }
       __syncthreads();

@@ -33,11 +33,16 @@ __global__ __launch_bounds__(256) void k_validate_b(int64_t rows, int64_t cols, 
     if (p > 0 && c <= col[p - 1]) ++flat;
   }
   if (bad) ctl->error = 1;
+  // one pair of atomics per workgroup: nearly every wave has descents to report (the row boundaries)
+  __shared__ int part[2][4];
   flat = wave_sum(flat);
   bnd = wave_sum(bnd);
-  if (lane_id() == 0) {
-    if (flat) atomicAdd(&ctl->desc_flat, (unsigned long long)flat);
-    if (bnd) atomicAdd(&ctl->desc_bnd, (unsigned long long)bnd);
+  if (lane_id() == 0) { part[0][threadIdx.x >> 6] = flat; part[1][threadIdx.x >> 6] = bnd; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const int f4 = part[0][0] + part[0][1] + part[0][2] + part[0][3], b4 = part[1][0] + part[1][1] + part[1][2] + part[1][3];
+    if (f4) atomicAdd(&ctl->desc_flat, (unsigned long long)f4);
+    if (b4) atomicAdd(&ctl->desc_bnd, (unsigned long long)b4);
   }
 }
 

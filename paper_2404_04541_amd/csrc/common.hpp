@@ -30,7 +30,7 @@ struct Control {
   unsigned hist[2][kNumBins];     // [0] symbolic, [1] numeric: rows per bin
   unsigned offset[2][kNumBins + 1];
   unsigned cursor[2][kNumBins];
-  unsigned work[4];               // dynamic work counters of the dense kernels
+  unsigned work[4];               // dynamic work counters: [0] dense symbolic rows, [1] dense numeric runs, [2] staged rows, [3] chunks of the row count
   unsigned tile_cursor, run_cursor;   // tile / run records written by the dense symbolic kernel
   unsigned tile_cap, run_cap;         // capacity of the two lists (set by the host)
   unsigned direct_tiles;              // how many of the tiles are direct

@@ -62,87 +62,95 @@ __global__ __launch_bounds__(kCountThreads) void k_count_rows(int64_t m, int64_t
   __shared__ unsigned long long hip[kNumBins];
   __shared__ int bad;
   const int tid = threadIdx.x;
-  const int64_t r0 = (int64_t)blockIdx.x * 256;
-  const int nr = (int)((m - r0) < 256 ? (m - r0) : 256);
   if (tid < kNumBins) { hist[tid] = 0; hip[tid] = 0; }
-  if (tid == 0) bad = 0;
-  for (int t = tid; t <= nr; t += kCountThreads) rp[t] = a_rp[r0 + t];
-  if (tid < 256) ipl[tid] = 0;
-  __syncthreads();
-  if (tid < nr && rp[tid + 1] < rp[tid]) bad = 1;
-  if (tid == 0) {
-    if (rp[0] < 0 || rp[nr] > nnz_a) bad = 1;
-    // (a block of rows of a larger matrix keeps that matrix's positions: it neither starts at 0 nor ends at nnz)
-    if (!row_block && r0 == 0 && rp[0] != 0) bad = 1;
-    if (!row_block && r0 + nr == m && rp[nr] != nnz_a) bad = 1;
-  }
-  __syncthreads();
-  if (bad) {
-    if (tid == 0) ctl->error = 1;
-    return;
-  }
-  const long long lo = rp[0], hi = rp[nr];
-  bool badcol = false;
-  // four entries per thread and round, so that their (dependent) loads overlap
-  for (long long p0 = lo + tid; p0 < hi; p0 += kCountThreads * 4) {
-    int k[4];
-    long long len[4];
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const long long p = p0 + u * kCountThreads;
-      k[u] = p < hi ? a_col[p] : -1;
+  // a workgroup takes several chunks and reports its bin populations once (thousands of workgroups adding to
+  // the same few counters cost more than the counting)
+  __shared__ long long next_chunk;
+  int64_t chunk = blockIdx.x;
+  while (chunk * 256 < m) {
+    // (the chunk after this one is drawn now and looked at when this one is done: chunks differ by orders of
+    // magnitude in their entries, so they are handed out rather than dealt)
+    long long drawn = 0;
+    if (tid == 0) drawn = (long long)gridDim.x + atomicAdd(&ctl->work[3], 1u);
+    const int64_t r0 = chunk * 256;
+    const int nr = (int)((m - r0) < 256 ? (m - r0) : 256);
+    __syncthreads();   // (the bin counters are initialised; the chunk before has left rp and ipl)
+    if (tid == 0) bad = 0;
+    for (int t = tid; t <= nr; t += kCountThreads) rp[t] = a_rp[r0 + t];
+    if (tid < 256) ipl[tid] = 0;
+    __syncthreads();
+    if (tid < nr && rp[tid + 1] < rp[tid]) bad = 1;
+    if (tid == 0) {
+      if (rp[0] < 0 || rp[nr] > nnz_a) bad = 1;
+      // (a block of rows of a larger matrix keeps that matrix's positions: it neither starts at 0 nor ends at nnz)
+      if (!row_block && r0 == 0 && rp[0] != 0) bad = 1;
+      if (!row_block && r0 + nr == m && rp[nr] != nnz_a) bad = 1;
     }
+    __syncthreads();
+    if (bad) {
+      if (tid == 0) ctl->error = 1;
+      return;
+    }
+    const long long lo = rp[0], hi = rp[nr];
+    bool badcol = false;
+    // four entries per thread and round, so that their (dependent) loads overlap
+    for (long long p0 = lo + tid; p0 < hi; p0 += kCountThreads * 4) {
+      int k[4];
+      long long len[4];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const long long p = p0 + u * kCountThreads;
-      len[u] = 0;
-      if (p < hi) {
-        if (k[u] < 0 || k[u] >= b_rows) { badcol = true; continue; }
-        const Run<int64_t, 2> bounds = load_run<int64_t, 2>(b_rp + k[u]);   // (both ends of the row in one load)
-        len[u] = bounds.v[1] - bounds.v[0];
-        if (len[u] < 0) { badcol = true; len[u] = 0; }
+      for (int u = 0; u < 4; ++u) {
+        const long long p = p0 + u * kCountThreads;
+        k[u] = p < hi ? a_col[p] : -1;
       }
-    }
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const long long p = p0 + u * kCountThreads;
-      if (len[u] > 0) {
-        // row of entry p: last t with rp[t] <= p
-        int a = 0, b = nr;
-        while (b - a > 1) {
-          const int mid = (a + b) >> 1;
-          if (rp[mid] <= p) a = mid; else b = mid;
+      for (int u = 0; u < 4; ++u) {
+        const long long p = p0 + u * kCountThreads;
+        len[u] = 0;
+        if (p < hi) {
+          if (k[u] < 0 || k[u] >= b_rows) { badcol = true; continue; }
+          const Run<int64_t, 2> bounds = load_run<int64_t, 2>(b_rp + k[u]);   // (both ends of the row in one load)
+          len[u] = bounds.v[1] - bounds.v[0];
+          if (len[u] < 0) { badcol = true; len[u] = 0; }
         }
-        atomicAdd(&ipl[a], (unsigned long long)len[u]);
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const long long p = p0 + u * kCountThreads;
+        if (len[u] > 0) {
+          // row of entry p: last t with rp[t] <= p
+          int a = 0, b = nr;
+          while (b - a > 1) {
+            const int mid = (a + b) >> 1;
+            if (rp[mid] <= p) a = mid; else b = mid;
+          }
+          atomicAdd(&ipl[a], (unsigned long long)len[u]);
+        }
       }
     }
+    if (badcol) ctl->error = 1;
+    __syncthreads();
+    if (tid < nr) {
+      const unsigned long long mine = ipl[tid];
+      const int bin = classify_symbolic((long long)mine, force);
+      ip_out[r0 + tid] = mine > 0x7fffffffULL ? 0x7fffffff : (int)mine;
+      bin_out[r0 + tid] = (unsigned char)bin;
+      if (bin == kEmptyBin) cnt_out[r0 + tid] = 0;
+      atomicAdd(&hist[bin], 1u);
+      if (mine) atomicAdd(&hip[bin], mine);
+    }
+    if (tid == 0) next_chunk = drawn;
+    __syncthreads();
+    chunk = next_chunk;
   }
-  if (badcol) ctl->error = 1;
   __syncthreads();
-  unsigned long long mine = 0;
-  if (tid < nr) {
-    mine = ipl[tid];
-    const int bin = classify_symbolic((long long)mine, force);
-    ip_out[r0 + tid] = mine > 0x7fffffffULL ? 0x7fffffff : (int)mine;
-    bin_out[r0 + tid] = (unsigned char)bin;
-    if (bin == kEmptyBin) cnt_out[r0 + tid] = 0;
-    atomicAdd(&hist[bin], 1u);
-    if (mine) atomicAdd(&hip[bin], mine);
-  }
-  // block total of ip
-  unsigned long long s = mine;
-  for (int d = 32; d > 0; d >>= 1) s += __shfl_xor(s, d, kWave);
-  __shared__ unsigned long long wsum[kCountThreads / kWave];
-  if ((tid & 63) == 0) wsum[tid >> 6] = s;
-  __syncthreads();
-  if (tid == 0) {
-    unsigned long long tot = 0;
-    for (int w = 0; w < kCountThreads / kWave; ++w) tot += wsum[w];
-    if (tot) atomicAdd(&ctl->ip_total, tot);
-  }
   if (tid < kNumBins && hist[tid]) {
     atomicAdd(&ctl->hist[0][tid], hist[tid]);
     if (hip[tid]) atomicAdd(&ctl->bin_ip[0][tid], hip[tid]);
+  }
+  if (tid == 0) {   // the products of all rows = the products of all bins
+    unsigned long long tot = 0;
+    for (int b = 0; b < kNumBins; ++b) tot += hip[b];
+    if (tot) atomicAdd(&ctl->ip_total, tot);
   }
 }
 

@@ -224,7 +224,7 @@ int run_setup(spgemm_context* h, spgemm_plan_s* p, const spgemm_csr* A, const sp
     hipLaunchKernelGGL(k_validate_b, dim3(grid_for(B->nnz > B->rows ? B->nnz : B->rows, 256 * 8, (int64_t)h->num_cus * 16)), dim3(256), 0, s,
                        B->rows, B->cols, B->nnz, B->rowptr, B->colidx, p->ctl);
     if (m > 0)
-      hipLaunchKernelGGL(k_count_rows, dim3((unsigned)ceil_div(m, 256)), dim3(kCountThreads), 0, s, m, A->nnz, B->rows, A->rowptr, A->colidx,
+      hipLaunchKernelGGL(k_count_rows, dim3(grid_for(m, 256, (int64_t)h->num_cus * 8)), dim3(kCountThreads), 0, s, m, A->nnz, B->rows, A->rowptr, A->colidx,
                          B->rowptr, p->ip, p->bin, p->cnt, p->ctl, h->force, h->row_block);
   }
   {
@@ -969,7 +969,7 @@ int spgemm_pipelined(spgemm_handle h, const spgemm_csr* A, const spgemm_csr* B, 
     Control host{};
     hipLaunchKernelGGL(k_init_control, dim3(1), dim3(64), 0, h->stream, ctl);
     if (m > 0)
-      hipLaunchKernelGGL(k_count_rows, dim3((unsigned)ceil_div(m, 256)), dim3(kCountThreads), 0, h->stream, m, A->nnz, B->rows, A->rowptr, A->colidx,
+      hipLaunchKernelGGL(k_count_rows, dim3(grid_for(m, 256, (int64_t)h->num_cus * 8)), dim3(kCountThreads), 0, h->stream, m, A->nnz, B->rows, A->rowptr, A->colidx,
                          B->rowptr, reinterpret_cast<int*>(tmp + o_ip), tmp + o_bin, reinterpret_cast<int*>(tmp + o_cnt), ctl, 0, 0);
     hipError_t e = hipGetLastError();
     if (e == hipSuccess && m > 0) e = hipMemcpyAsync(ip_host.data(), tmp + o_ip, (size_t)m * 4, hipMemcpyDeviceToHost, h->stream);

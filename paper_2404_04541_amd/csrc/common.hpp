@@ -33,6 +33,7 @@ struct Control {
   unsigned work[4];               // dynamic work counters: [0] dense symbolic rows, [1] dense numeric runs, [2] staged rows, [3] chunks of the row count
   unsigned tile_cursor, run_cursor;   // tile / run records written by the dense symbolic kernel
   unsigned tile_cap, run_cap;         // capacity of the two lists (set by the host)
+  unsigned tiles_used, runs_used;     // records in use (the cursors also count what is left of the workgroups' slabs)
   unsigned direct_tiles;              // how many of the tiles are direct
   unsigned search_tiles;              // how many are searched tiles
   unsigned long long list_cursor, list_cap;   // entries used / available in the plan's column list

@@ -40,6 +40,9 @@ constexpr int kRankBlkBytes = kBlkCols / 32 * 8;   // flag word + rank per 32 co
 constexpr int kRankEntryBytes = 8;                // sum per entry of a ranked tile (its column goes straight to C)
 constexpr int kDirectMinDefault = 6144; // a block with at least this many entries becomes a direct tile
 constexpr int kRunTiles = 16;           // tiles handed to a workgroup at a time
+constexpr int kListSlab = 1 << 20;      // list entries, tile and run records that a symbolic workgroup draws at a time
+constexpr int kTileSlab = 2048;
+constexpr int kRunSlab = 256;
 constexpr int kDirectBit = 1 << 30;     // in TileRec::cnt
 constexpr int kSearchBit = 1 << 29;     // in TileRec::cnt: a searched tile (ranks by bisection of the column list)
 constexpr int kCountMask = kSearchBit - 1;
@@ -461,6 +464,19 @@ __device__ __forceinline__ void plan_tail(TilePlan* tp, int nb, int block0, int 
   }
 }
 
+// Takes `amount` from a shared cursor if that stays within `cap` (compare and advance: the cursor never
+// passes the capacity, so a request that does not fit costs later, smaller requests nothing).
+__device__ __forceinline__ bool reserve_below(unsigned long long* cursor, unsigned long long amount, unsigned long long cap,
+                                              unsigned long long& base) {
+  unsigned long long cur = __hip_atomic_load(cursor, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  while (cur + amount <= cap) {
+    const unsigned long long seen = atomicCAS(cursor, cur, cur + amount);
+    if (seen == cur) { base = cur; return true; }
+    cur = seen;
+  }
+  return false;
+}
+
 // Fetch the next row of the dense symbolic bins (4..6), heaviest class first; -1 when none is left.
 __device__ __forceinline__ int next_dense_row(const int* __restrict__ perm, Control* ctl, int* s_row) {
   __syncthreads();
@@ -494,7 +510,14 @@ __global__ __launch_bounds__(kDenseThreads) void k_sym_dense(const int* __restri
   SPG_CLK(clk_begin(&rs->clk);)
   int row = next_dense_row(perm, ctl, &rs->s_row);
   int next_row = -1;   // (thread 0) the row after this one, fetched while this one is in the works
+  // (thread 0) what is left of the slabs drawn from the plan's lists, and what this workgroup used
+  unsigned long long sl_pos = 0, sl_left = 0;
+  // (slabs of the list: together at most a quarter of it, so that a short list is not spent on slack)
+  const unsigned long long list_slab = list_cap / (4ULL * gridDim.x) < (unsigned long long)kListSlab ? (list_cap / (4ULL * gridDim.x)) & ~3ULL : (unsigned long long)kListSlab;
+  unsigned st_pos = 0, st_left = 0, sr_pos = 0, sr_left = 0, used_tiles = 0, used_runs = 0;
   while (row >= 0) {
+    unsigned nx = 0;   // (thread 0) the draw for the row after this one: on its way while this row is in the works
+    if (tid == 0) nx = atomicAdd(&ctl->work[0], 1u);
     const int64_t a0 = a_rp[row];
     const int d = (int)(a_rp[row + 1] - a0);
     if (tid == 0) tp->row_out = 0;
@@ -591,20 +614,49 @@ __global__ __launch_bounds__(kDenseThreads) void k_sym_dense(const int* __restri
         const bool as_words = !search_row && (long long)fwords * kFlagWordsNum <= (long long)kFlagWordsDen * total;
         const unsigned long long need = as_words ? (unsigned long long)(span_rank_slots(words) + fwords)
                                                  : (unsigned long long)((total + 3) & ~3);   // (16-byte granules)
+        // The shares come out of slabs that the workgroup draws from the shared cursors now and then: a round
+        // trip to a counter that every workgroup hits costs microseconds, a row needs its answer at once.
         unsigned long long at = 0;
-        unsigned tb = 0, rb = 0, nx = 0;
-        if (want_list) at = atomicAdd(&ctl->list_cursor, need);
-        if (nt > 0) { tb = atomicAdd(&ctl->tile_cursor, (unsigned)nt); rb = atomicAdd(&ctl->run_cursor, (unsigned)nr); }
-        if (last_span) nx = atomicAdd(&ctl->work[0], 1u);
-        const bool listed = want_list && at + need <= list_cap;
-        if (want_list && !listed) atomicAdd(&ctl->list_cursor, 0ULL - need);   // (no room: the share goes back, later rows may still fit)
+        unsigned tb = 0, rb = 0;
+        bool listed = false;
+        if (want_list) {
+          if (need <= sl_left) {
+            at = sl_pos; sl_pos += need; sl_left -= need; listed = true;
+          } else {   // (what is left of the old slab stays unused)
+            const unsigned long long grab = need > list_slab ? need : list_slab;
+            unsigned long long base;
+            if (reserve_below(&ctl->list_cursor, grab, list_cap, base)) {
+              at = base; sl_pos = base + need; sl_left = grab - need; listed = true;
+            } else if (grab != need && reserve_below(&ctl->list_cursor, need, list_cap, base)) {
+              at = base; listed = true;   // (no room for a slab, but for the row alone)
+            }
+          }
+        }
+        bool room = true;
+        if (nt > 0) {
+          if ((unsigned)nt > st_left) {
+            st_pos = atomicAdd(&ctl->tile_cursor, (unsigned)kTileSlab);
+            room = st_pos + (unsigned)kTileSlab <= tile_cap;
+            st_left = room ? (unsigned)kTileSlab : 0u;
+          }
+          if (room && (unsigned)nr > sr_left) {
+            for (unsigned i = 0; i < sr_left; ++i) runs[sr_pos + i].count = 0;   // (slots left behind: empty records)
+            sr_pos = atomicAdd(&ctl->run_cursor, (unsigned)kRunSlab);
+            room = sr_pos + (unsigned)kRunSlab <= run_cap;
+            sr_left = room ? (unsigned)kRunSlab : 0u;
+          }
+          if (room) {
+            tb = st_pos; st_pos += (unsigned)nt; st_left -= (unsigned)nt;
+            rb = sr_pos; sr_pos += (unsigned)nr; sr_left -= (unsigned)nr;
+          }
+        }
         tp->list_base = listed ? (long long)at : -1;
         tp->list_words = listed && as_words ? fwords : 0;
         tp->tile_base = tb;
         tp->run_base = rb;
         tp->next_block = 0;
         tp->nruns = nr;
-        if (nt > 0 && (tb + (unsigned)nt > tile_cap || rb + (unsigned)nr > run_cap)) {
+        if (nt > 0 && !room) {
           ctl->error = 3;   // cannot happen when the host sized the lists from the bound
           tp->ntiles = 0;
           tp->nruns = 0;
@@ -617,6 +669,8 @@ __global__ __launch_bounds__(kDenseThreads) void k_sym_dense(const int* __restri
         } else if (tp->ndirect > 0) {
           atomicAdd(&ctl->direct_tiles, (unsigned)tp->ndirect);
         }
+        used_tiles += (unsigned)tp->ntiles;
+        used_runs += (unsigned)tp->nruns;
         if (last_span) next_row = nx < row_hi - row_lo ? perm[row_hi - 1 - nx] : -1;
       }
       __syncthreads();
@@ -729,6 +783,11 @@ __global__ __launch_bounds__(kDenseThreads) void k_sym_dense(const int* __restri
     }
     __syncthreads();
     row = rs->s_row;
+  }
+  if (tid == 0) {
+    for (unsigned i = 0; i < sr_left; ++i) runs[sr_pos + i].count = 0;
+    if (used_tiles) atomicAdd(&ctl->tiles_used, used_tiles);
+    if (used_runs) atomicAdd(&ctl->runs_used, used_runs);
   }
   SPG_CLK(clk_mark(&rs->clk, 9); clk_flush(&rs->clk, ctl->clk[0]);)
 }

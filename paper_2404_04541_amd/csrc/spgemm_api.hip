@@ -256,8 +256,10 @@ int alloc_dense_lists(spgemm_context* h, spgemm_plan_s* p, const spgemm_csr* B, 
   if (ip_d / h->direct_min < direct) direct = ip_d / h->direct_min;
   const double entries = ip_d < rows_d * n ? ip_d : rows_d * n;
   const double weight = rows_d * blocks * kRankBlkBytes + (double)kRankEntryBytes * entries;
-  const double tiles = 2.0 * direct + 2.0 * weight / kTileBudget + 4.0 * rows_d * spans + 16.0;
-  const double runs = tiles / kRunTiles + rows_d * spans + 16.0;
+  // (+ a slab per workgroup of the symbolic kernel: what a workgroup has drawn and not used)
+  const double wgs = (double)grid_for((int64_t)rows_d, 1, h->num_cus) + 1.0;
+  const double tiles = 2.0 * direct + 2.0 * weight / kTileBudget + 4.0 * rows_d * spans + 16.0 + wgs * kTileSlab;
+  const double runs = (tiles - wgs * kTileSlab) / kRunTiles + rows_d * spans + 16.0 + wgs * kRunSlab;
   if (tiles > 4.0e9) return fail(h, SPGEMM_UNSUPPORTED, "tile list of the dense workspace would exceed 2^32 records");
   *tile_cap = (unsigned)tiles;
   *run_cap = (unsigned)runs;
@@ -598,9 +600,9 @@ int spgemm_symbolic(spgemm_handle h, const spgemm_csr* A, const spgemm_csr* B, i
     p->stats.num_bin_ip[b] = (int64_t)host.bin_ip[1][b];
     p->stats.num_bin_nnz[b] = (int64_t)host.bin_nnz[b];
   }
-  p->stats.dense_tiles = host.tile_cursor;
+  p->stats.dense_tiles = host.tiles_used;
   p->stats.dense_direct_tiles = host.direct_tiles;
-  p->stats.dense_runs = host.run_cursor;
+  p->stats.dense_runs = host.runs_used;
   p->stats.dense_search_tiles = host.search_tiles;
   p->stats.plan_bytes = (int64_t)(p->scratch_bytes + p->scratch2_bytes + p->scratch3_bytes);
   p->stats.plan_list_bytes = (int64_t)p->scratch3_bytes;
